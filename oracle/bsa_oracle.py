@@ -1,0 +1,230 @@
+"""ctypes front end of the CPU oracle (oracle/bsa_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The product package never imports this module,
+and this module never imports the product package.
+
+All tensors are numpy arrays: fp32 [B, heads, N, D] inputs (bf16 data widened
+exactly to fp32 by the caller), int32 [B, heads, m, n] selections, float64
+outputs.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bsa_oracle.c")
+_LIB = os.path.join(_HERE, "libbsa_oracle.so")
+_lib = None
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int32) for name in (
+        "batch", "heads", "grid_h", "grid_w", "block_h", "block_w",
+        "head_dim", "n_select")]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or \
+            os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call([
+            "gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fopenmp",
+            "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_token_of.restype = ctypes.c_int64
+        _lib.oracle_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _shape(batch, heads, grid_h, grid_w, block_h, block_w, head_dim, n_select):
+    if grid_h % block_h or grid_w % block_w:
+        raise ValueError("tile must divide the grid")
+    m = (grid_h // block_h) * (grid_w // block_w)
+    if not 0 <= n_select <= m - 1:
+        raise ValueError("n_select must be in [0, m-1]")
+    return _Shape(batch, heads, grid_h, grid_w, block_h, block_w, head_dim,
+                  n_select)
+
+
+def shape_of(cfg, n_select=None):
+    """oracle shape from any object with the grid-configuration attributes."""
+    return _shape(cfg.batch, cfg.heads, cfg.grid_h, cfg.grid_w, cfg.block_h,
+                  cfg.block_w, cfg.head_dim,
+                  cfg.n_select if n_select is None else n_select)
+
+
+def _f32(x):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    return x, x.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(x):
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    return x, x.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dims(s):
+    N = s.grid_h * s.grid_w
+    b = s.block_h * s.block_w
+    return s.batch, s.heads, N, s.head_dim, b, N // b
+
+
+def _check(s, *tensors):
+    B, h, N, D, _, _ = _dims(s)
+    for t in tensors:
+        if t.shape != (B, h, N, D):
+            raise ValueError(f"expected {(B, h, N, D)}, got {t.shape}")
+
+
+def threads() -> int:
+    return int(_load().oracle_threads())
+
+
+def token_of(s, beta: int, tau: int) -> int:
+    return int(_load().oracle_token_of(ctypes.byref(s), int(beta), int(tau)))
+
+
+def pool(s, x):
+    """Mean-pooled block representations, fp32 [B, heads, m, D]."""
+    B, h, N, D, b, m = _dims(s)
+    x, px = _f32(x)
+    _check(s, x)
+    out = np.empty((B, h, m, D), dtype=np.float32)
+    _load().oracle_pool(ctypes.byref(s), px, out.ctypes.data_as(ctypes.c_void_p))
+    return out
+
+
+def scores(s, qbar, kbar):
+    """Block-level scores, fp32 [B, heads, m, m] (diagonal included)."""
+    B, h, N, D, b, m = _dims(s)
+    qbar, pq = _f32(qbar)
+    kbar, pk = _f32(kbar)
+    out = np.empty((B, h, m, m), dtype=np.float32)
+    _load().oracle_scores(ctypes.byref(s), pq, pk,
+                          out.ctypes.data_as(ctypes.c_void_p))
+    return out
+
+
+def select_from_pooled(s, qbar, kbar):
+    B, h, N, D, b, m = _dims(s)
+    qbar, pq = _f32(qbar)
+    kbar, pk = _f32(kbar)
+    assert qbar.shape == (B, h, m, D) and kbar.shape == (B, h, m, D)
+    idx = np.empty((B, h, m, s.n_select), dtype=np.int32)
+    _load().oracle_select_from_pooled(ctypes.byref(s), pq, pk,
+                                      idx.ctypes.data_as(ctypes.c_void_p))
+    return idx
+
+
+def select(s, q, k):
+    """Selected block indices, int32 [B, heads, m, n]."""
+    B, h, N, D, b, m = _dims(s)
+    q, pq = _f32(q)
+    k, pk = _f32(k)
+    _check(s, q, k)
+    idx = np.empty((B, h, m, s.n_select), dtype=np.int32)
+    _load().oracle_select(ctypes.byref(s), pq, pk,
+                          idx.ctypes.data_as(ctypes.c_void_p))
+    return idx
+
+
+def fwd(s, q, k, v, sel_idx, scale: float = 0.0):
+    """Attention output and log-sum-exp, float64 ([B,h,N,D], [B,h,N])."""
+    B, h, N, D, b, m = _dims(s)
+    q, pq = _f32(q)
+    k, pk = _f32(k)
+    v, pv = _f32(v)
+    _check(s, q, k, v)
+    sel_idx, pi = _i32(sel_idx)
+    assert sel_idx.shape == (B, h, m, s.n_select)
+    out = np.empty((B, h, N, D), dtype=np.float64)
+    lse = np.empty((B, h, N), dtype=np.float64)
+    _load().oracle_fwd(ctypes.byref(s), pq, pk, pv, pi, ctypes.c_double(scale),
+                       out.ctypes.data_as(ctypes.c_void_p),
+                       lse.ctypes.data_as(ctypes.c_void_p))
+    return out, lse
+
+
+def fwd_blocks(s, q, k, v, sel_idx, pairs, scale: float = 0.0):
+    """Forward for the listed (batch*head, block) pairs only.
+
+    Returns (out [cnt, b, D], lse [cnt, b]) float64 with rows in in-tile order.
+    """
+    B, h, N, D, b, m = _dims(s)
+    q, pq = _f32(q)
+    k, pk = _f32(k)
+    v, pv = _f32(v)
+    _check(s, q, k, v)
+    sel_idx, pi = _i32(sel_idx)
+    pairs = np.ascontiguousarray(pairs, dtype=np.int64).reshape(-1, 2)
+    # the C routine writes rows in place of a full-size output; keep only the
+    # batch*head slices that are touched
+    gs = np.unique(pairs[:, 0])
+    remap = {int(g): r for r, g in enumerate(gs)}
+    sub = _shape(1, len(gs), s.grid_h, s.grid_w, s.block_h, s.block_w, D,
+                 s.n_select)
+    q_s = np.ascontiguousarray(q.reshape(B * h, N, D)[gs])
+    k_s = np.ascontiguousarray(k.reshape(B * h, N, D)[gs])
+    v_s = np.ascontiguousarray(v.reshape(B * h, N, D)[gs])
+    i_s = np.ascontiguousarray(sel_idx.reshape(B * h, m, s.n_select)[gs])
+    p_s = np.array([[remap[int(g)], i] for g, i in pairs], dtype=np.int64)
+    out = np.zeros((len(gs), N, D), dtype=np.float64)
+    lse = np.zeros((len(gs), N), dtype=np.float64)
+    _load().oracle_fwd_blocks(
+        ctypes.byref(sub), q_s.ctypes.data_as(ctypes.c_void_p),
+        k_s.ctypes.data_as(ctypes.c_void_p), v_s.ctypes.data_as(ctypes.c_void_p),
+        i_s.ctypes.data_as(ctypes.c_void_p), ctypes.c_double(scale),
+        p_s.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(len(p_s)),
+        out.ctypes.data_as(ctypes.c_void_p), lse.ctypes.data_as(ctypes.c_void_p))
+    rows = np.array([[token_of(s, int(i), t) for t in range(b)]
+                     for _, i in pairs], dtype=np.int64)
+    gsel = p_s[:, 0][:, None]
+    return out[gsel, rows], lse[gsel, rows]
+
+
+def block_weights(s, q, k, v, sel_idx, g: int, i: int, scale: float = 0.0):
+    """Attention weights P [b, (n+1)*b] of query block i of batch*head g;
+    column c*b + tau is token tau of the c-th attended block (c = 0: itself)."""
+    B, h, N, D, b, m = _dims(s)
+    q, pq = _f32(q)
+    k, pk = _f32(k)
+    v, pv = _f32(v)
+    sel_idx, pi = _i32(sel_idx)
+    P = np.empty((b, (s.n_select + 1) * b), dtype=np.float64)
+    _load().oracle_block_weights(ctypes.byref(s), pq, pk, pv, pi,
+                                 ctypes.c_double(scale), ctypes.c_int64(g),
+                                 ctypes.c_int(i),
+                                 P.ctypes.data_as(ctypes.c_void_p))
+    return P
+
+
+def bwd(s, q, k, v, dout, sel_idx, scale: float = 0.0):
+    """dQ, dK, dV (float64 [B,h,N,D]) with the selection held fixed."""
+    B, h, N, D, b, m = _dims(s)
+    q, pq = _f32(q)
+    k, pk = _f32(k)
+    v, pv = _f32(v)
+    dout, pd = _f32(dout)
+    _check(s, q, k, v, dout)
+    sel_idx, pi = _i32(sel_idx)
+    dq = np.empty((B, h, N, D), dtype=np.float64)
+    dk = np.empty_like(dq)
+    dv = np.empty_like(dq)
+    _load().oracle_bwd(ctypes.byref(s), pq, pk, pv, pd, pi,
+                       ctypes.c_double(scale),
+                       dq.ctypes.data_as(ctypes.c_void_p),
+                       dk.ctypes.data_as(ctypes.c_void_p),
+                       dv.ctypes.data_as(ctypes.c_void_p))
+    return dq, dk, dv

@@ -1,0 +1,392 @@
+"""Pins of the CPU oracle against facts fixed by the paper and by mathematics.
+
+None of these tests touches the GPU library.  Each one is chosen so that a
+plausible mistake in the oracle (wrong tile index, dropped block, missing
+scale, wrong sign in the gradient, transposed operand, wrong tie-break ...)
+fails it.  Citations name the paper's Block-Sparse Attention subsection.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from tests.helpers import (from_tiles, rand_qkv, random_selection, shape_ns,
+                           to_tiles)
+
+torch.set_num_threads(4)
+
+
+# --------------------------------------------------------------------------
+# partition (Compression paragraph: m non-overlapping blocks)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("H,W,bh,bw", [(16, 24, 8, 8), (8, 32, 4, 16), (6, 6, 2, 3)])
+def test_partition_is_a_bijection_and_matches_reshape(oracle, H, W, bh, bw):
+    c = shape_ns(1, 1, H, W, bh, bw, 1, 0)
+    s = oracle.shape_of(c)
+    toks = np.array([[oracle.token_of(s, i, t) for t in range(c.block_tokens)]
+                     for i in range(c.n_blocks)])
+    assert sorted(toks.ravel().tolist()) == list(range(H * W))
+    grid = np.arange(H * W, dtype=np.float32).reshape(1, 1, H * W, 1)
+    assert np.array_equal(to_tiles(grid, c)[0, 0, :, :, 0].astype(np.int64), toks)
+    # tokens of a block are spatial neighbours: a bh x bw rectangle
+    r, col = toks // W, toks % W
+    assert np.all(r.max(1) - r.min(1) == bh - 1)
+    assert np.all(col.max(1) - col.min(1) == bw - 1)
+
+
+# --------------------------------------------------------------------------
+# pooling equation (phi = mean)
+# --------------------------------------------------------------------------
+def test_pool_constant_and_block_id_fields(oracle):
+    c = shape_ns(2, 2, 16, 32, 8, 8, 4, 0)
+    s = oracle.shape_of(c)
+    x = np.full((2, 2, c.n_tokens, 4), 0.3, dtype=np.float32)
+    # 64 adds of 0.3f are not exact, but a power-of-two constant is
+    x[:] = 0.375
+    assert np.all(oracle.pool(s, x) == np.float32(0.375))
+    ids = np.arange(c.n_blocks, dtype=np.float32)
+    tiles = np.broadcast_to(ids[None, None, :, None, None],
+                            (2, 2, c.n_blocks, c.block_tokens, 4))
+    pooled = oracle.pool(s, from_tiles(np.ascontiguousarray(tiles), c))
+    assert np.array_equal(pooled, np.broadcast_to(ids[None, None, :, None],
+                                                  pooled.shape))
+
+
+def test_pool_plus_minus_pairs_vanish_and_matches_float64_mean(oracle):
+    c = shape_ns(1, 3, 24, 16, 8, 8, 5, 0)
+    s = oracle.shape_of(c)
+    rng = np.random.default_rng(1)
+    tiles = rng.standard_normal((1, 3, c.n_blocks, c.block_tokens, 5)).astype(np.float32)
+    tiles[..., 1::2, :] = -tiles[..., 0::2, :]
+    assert np.all(oracle.pool(s, from_tiles(tiles, c)) == 0.0)
+    x = rng.standard_normal((1, 3, c.n_tokens, 5)).astype(np.float32)
+    ref = to_tiles(x, c).astype(np.float64).mean(axis=3)
+    np.testing.assert_allclose(oracle.pool(s, x), ref, rtol=0, atol=2e-6)
+
+
+def test_pool_and_scores_exact_in_the_quantised_regime(oracle):
+    """Inputs on a 1/4 grid in [-2, 2], b = 64, D = 32: every partial sum,
+    mean and partial score fits fp32 exactly, so the oracle must reproduce
+    integer arithmetic bit for bit, whatever the summation order."""
+    c = shape_ns(1, 2, 32, 64, 8, 8, 32, 4)
+    s = oracle.shape_of(c)
+    rng = np.random.default_rng(2)
+    qi = rng.integers(-8, 9, size=(1, 2, c.n_tokens, 32))
+    ki = rng.integers(-8, 9, size=(1, 2, c.n_tokens, 32))
+    q, k = (qi / 4).astype(np.float32), (ki / 4).astype(np.float32)
+    qsum = to_tiles(qi, c).sum(axis=3)          # integers, units of 1/4
+    ksum = to_tiles(ki, c).sum(axis=3)
+    qbar, kbar = oracle.pool(s, q), oracle.pool(s, k)
+    assert np.array_equal(qbar.astype(np.float64) * 256, qsum)   # mean = sum/(4*64)
+    assert np.array_equal(kbar.astype(np.float64) * 256, ksum)
+    sc = oracle.scores(s, qbar, kbar)
+    exact = np.einsum("ghid,ghjd->ghij", qsum, ksum)             # units of 2^-16
+    assert np.array_equal(sc.astype(np.float64) * 65536, exact)
+    # ranking by exact integers == oracle selection, with the tie-break rule
+    idx = oracle.select(s, q, k)
+    for a in range(2):
+        for i in range(c.n_blocks):
+            cand = [j for j in range(c.n_blocks) if j != i]
+            cand.sort(key=lambda j: (-int(exact[0, a, i, j]), j))
+            assert idx[0, a, i].tolist() == cand[:4]
+
+
+def test_scores_agree_with_exact_rational_arithmetic(oracle):
+    c = shape_ns(1, 1, 8, 16, 2, 4, 8, 3)
+    s = oracle.shape_of(c)
+    q, k, _ = rand_qkv(c, 3)
+    qbar, kbar = oracle.pool(s, q), oracle.pool(s, k)
+    sc = oracle.scores(s, qbar, kbar)[0, 0]
+    idx = oracle.select(s, q, k)[0, 0]
+    m = c.n_blocks
+    fq = [[Fraction(float(x)) for x in row] for row in qbar[0, 0]]
+    fk = [[Fraction(float(x)) for x in row] for row in kbar[0, 0]]
+    for i in range(m):
+        ex = [sum(a * b for a, b in zip(fq[i], fk[j])) for j in range(m)]
+        mag = [sum(abs(a * b) for a, b in zip(fq[i], fk[j])) for j in range(m)]
+        for j in range(m):
+            # fused chain of D terms: error <= D * 2^-24 * sum |terms|
+            assert abs(Fraction(float(sc[i, j])) - ex[j]) <= 8 * Fraction(1, 2 ** 24) * mag[j]
+        cand = sorted((j for j in range(m) if j != i), key=lambda j: (-ex[j], j))
+        gap = min(ex[cand[r]] - ex[cand[r + 1]] for r in range(3))
+        if gap > 16 * Fraction(1, 2 ** 24) * max(mag):
+            assert idx[i].tolist() == cand[:3]
+
+
+# --------------------------------------------------------------------------
+# selection (Selection paragraph: top-n of the block-level scores)
+# --------------------------------------------------------------------------
+def test_planted_selection_follows_the_planted_ranking(oracle):
+    c = shape_ns(1, 2, 16, 32, 4, 4, 8, 5)
+    s = oracle.shape_of(c)
+    m = c.n_blocks
+    rng = np.random.default_rng(4)
+    u = rng.integers(1, 4, size=8).astype(np.float32)            # positive direction
+    alpha = rng.permutation(m).astype(np.float32) - 7.0          # distinct integers
+    ktiles = np.broadcast_to((alpha[:, None, None] * u)[None, None],
+                             (1, 2, m, c.block_tokens, 8))
+    qtiles = np.broadcast_to(u[None, None, None, None, :], (1, 2, m, c.block_tokens, 8))
+    k = from_tiles(np.ascontiguousarray(ktiles, dtype=np.float32), c)
+    q = from_tiles(np.ascontiguousarray(qtiles, dtype=np.float32), c)
+    idx = oracle.select(s, q, k)
+    order = np.argsort(-alpha, kind="stable")
+    for i in range(m):
+        want = [j for j in order if j != i][:5]
+        assert idx[0, 0, i].tolist() == want and idx[0, 1, i].tolist() == want
+    # flipping the sign of Q reverses the ranking (a lost sign would not)
+    idx_neg = oracle.select(s, -q, k)
+    order_neg = np.argsort(alpha, kind="stable")
+    for i in range(m):
+        assert idx_neg[0, 0, i].tolist() == [j for j in order_neg if j != i][:5]
+
+
+def test_all_ties_give_smallest_indices_excluding_self(oracle):
+    c = shape_ns(1, 1, 16, 16, 4, 4, 4, 6)
+    s = oracle.shape_of(c)
+    q, _, _ = rand_qkv(c, 5)
+    k = np.ones_like(q)
+    idx = oracle.select(s, q, k)[0, 0]
+    for i in range(c.n_blocks):
+        assert idx[i].tolist() == [j for j in range(c.n_blocks) if j != i][:6]
+
+
+def test_selection_invariances(oracle):
+    c = shape_ns(1, 2, 32, 32, 8, 8, 16, 4)
+    s = oracle.shape_of(c)
+    q, k, _ = rand_qkv(c, 6)
+    idx = oracle.select(s, q, k)
+    # power-of-two scaling of Q is exact in fp32: ranking unchanged
+    assert np.array_equal(oracle.select(s, q * 8.0, k), idx)
+    assert np.array_equal(oracle.select(s, q, k * 0.25), idx)
+    # rows: n distinct indices, never the block itself, all in range
+    m = c.n_blocks
+    assert idx.min() >= 0 and idx.max() < m
+    for a in range(2):
+        for i in range(m):
+            row = idx[0, a, i].tolist()
+            assert i not in row and len(set(row)) == 4
+    # only pooled means matter: quantised data + zero-mean pattern per tile
+    rng = np.random.default_rng(7)
+    qq = (rng.integers(-8, 9, size=q.shape) / 4).astype(np.float32)
+    kq = (rng.integers(-8, 9, size=q.shape) / 4).astype(np.float32)
+    pat = (rng.integers(-4, 5, size=(1, 2, m, 32, 16)) / 4).astype(np.float32)
+    pat = np.concatenate([pat, -pat], axis=3)                    # sums to 0 per tile
+    base = oracle.select(s, qq, kq)
+    assert np.array_equal(oracle.select(s, qq, kq + from_tiles(pat, c)), base)
+
+
+def test_select_equals_sorting_the_oracle_scores(oracle):
+    """Top-n emitted == full sort of every candidate by (score desc, index asc)."""
+    c = shape_ns(2, 2, 16, 32, 4, 4, 8, 7)
+    s = oracle.shape_of(c)
+    q, k, _ = rand_qkv(c, 8)
+    sc = oracle.scores(s, oracle.pool(s, q), oracle.pool(s, k))
+    idx = oracle.select(s, q, k)
+    for e in range(2):
+        for a in range(2):
+            for i in range(c.n_blocks):
+                js = np.array([j for j in range(c.n_blocks) if j != i])
+                order = np.lexsort((js, -sc[e, a, i, js].astype(np.float64)))
+                assert idx[e, a, i].tolist() == js[order][:7].tolist()
+
+
+# --------------------------------------------------------------------------
+# attention (fine-grained attention equation + local block, one softmax)
+# --------------------------------------------------------------------------
+def _sdpa(q, k, v, scale=None):
+    return torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).double(), torch.from_numpy(k).double(),
+        torch.from_numpy(v).double(), scale=scale).numpy()
+
+
+def test_all_blocks_selected_is_dense_attention(oracle):
+    c = shape_ns(2, 2, 8, 16, 4, 4, 16, 7)     # m = 8, n = m - 1
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 9)
+    idx = oracle.select(s, q, k)
+    out, lse = oracle.fwd(s, q, k, v, idx)
+    np.testing.assert_allclose(out, _sdpa(q, k, v), rtol=0, atol=1e-12)
+    z = np.einsum("ghld,ghtd->ghlt", q.astype(np.float64), k.astype(np.float64)) / 4.0
+    np.testing.assert_allclose(
+        lse, torch.logsumexp(torch.from_numpy(z), dim=-1).numpy(), rtol=0, atol=1e-12)
+    # any order of the selected blocks gives the same result
+    out2, _ = oracle.fwd(s, q, k, v, random_selection(c, 10))
+    np.testing.assert_allclose(out2, out, rtol=0, atol=1e-13)
+    # explicit scale argument is honoured
+    out3, _ = oracle.fwd(s, q, k, v, idx, scale=0.7)
+    np.testing.assert_allclose(out3, _sdpa(q, k, v, scale=0.7), rtol=0, atol=1e-12)
+
+
+def test_no_selection_is_block_diagonal_attention(oracle):
+    c = shape_ns(1, 2, 8, 12, 4, 3, 8, 0)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 11)
+    idx = np.zeros((1, 2, c.n_blocks, 0), dtype=np.int32)
+    out, _ = oracle.fwd(s, q, k, v, idx)
+    ref = _sdpa(to_tiles(q, c), to_tiles(k, c), to_tiles(v, c))
+    np.testing.assert_allclose(to_tiles(out, c), ref, rtol=0, atol=1e-12)
+
+
+def test_sparse_attention_equals_library_attention_over_gathered_tiles(oracle):
+    """For an arbitrary valid selection, each query tile's result equals plain
+    softmax attention over the concatenation of its own and its selected
+    tiles (gathered here by reshape, not by the oracle's index formula)."""
+    c = shape_ns(2, 2, 12, 16, 4, 4, 8, 3)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 12, scale=1.5)
+    idx = random_selection(c, 13)
+    out, lse = oracle.fwd(s, q, k, v, idx)
+    qt, kt, vt, ot = (to_tiles(x, c) for x in (q, k, v, out))
+    lt = to_tiles(lse[..., None], c)[..., 0]
+    for e in range(2):
+        for a in range(2):
+            for i in range(c.n_blocks):
+                blocks = [i] + idx[e, a, i].tolist()
+                kk = np.concatenate([kt[e, a, j] for j in blocks])
+                vv = np.concatenate([vt[e, a, j] for j in blocks])
+                np.testing.assert_allclose(ot[e, a, i], _sdpa(qt[e, a, i], kk, vv),
+                                           rtol=0, atol=1e-12)
+                z = qt[e, a, i].astype(np.float64) @ kk.astype(np.float64).T / np.sqrt(8.0)
+                ref_lse = torch.logsumexp(torch.from_numpy(z), dim=-1).numpy()
+                np.testing.assert_allclose(lt[e, a, i], ref_lse, rtol=0, atol=1e-12)
+
+
+def test_rows_sum_to_one(oracle):
+    c = shape_ns(1, 2, 16, 16, 4, 4, 8, 5)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 14, scale=2.0)
+    idx = oracle.select(s, q, k)
+    const = np.linspace(-1, 1, 8).astype(np.float32)
+    out, _ = oracle.fwd(s, q, k, np.broadcast_to(const, v.shape).copy(), idx)
+    np.testing.assert_allclose(out, np.broadcast_to(const.astype(np.float64), out.shape),
+                               rtol=0, atol=1e-14)
+    P = oracle.block_weights(s, q, k, v, idx, 1, 3)
+    assert P.shape == (16, 6 * 16) and np.all(P >= 0)
+    np.testing.assert_allclose(P.sum(axis=1), 1.0, rtol=0, atol=1e-14)
+
+
+def test_unselected_blocks_do_not_matter(oracle):
+    c = shape_ns(1, 1, 16, 16, 4, 4, 8, 3)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 15)
+    idx = oracle.select(s, q, k)
+    out, lse = oracle.fwd(s, q, k, v, idx)
+    i = 5
+    untouched = [j for j in range(c.n_blocks) if j != i and j not in idx[0, 0, i]]
+    kt, vt = to_tiles(k, c).copy(), to_tiles(v, c).copy()
+    kt[0, 0, untouched] = 7.0
+    vt[0, 0, untouched] = -3.0
+    out2, lse2 = oracle.fwd(s, q, from_tiles(kt, c), from_tiles(vt, c), idx)
+    assert np.array_equal(to_tiles(out, c)[0, 0, i], to_tiles(out2, c)[0, 0, i])
+    # ... while a selected block does
+    kt2 = to_tiles(k, c).copy()
+    kt2[0, 0, idx[0, 0, i, 0]] += 1.0
+    out3, _ = oracle.fwd(s, q, from_tiles(kt2, c), v, idx)
+    assert not np.array_equal(to_tiles(out, c)[0, 0, i], to_tiles(out3, c)[0, 0, i])
+
+
+def test_single_token_blocks_without_selection_return_v(oracle):
+    c = shape_ns(1, 1, 4, 4, 1, 1, 8, 0)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 16)
+    out, lse = oracle.fwd(s, q, k, v, np.zeros((1, 1, 16, 0), np.int32))
+    assert np.array_equal(out, v.astype(np.float64))
+    z = (q.astype(np.float64) * k.astype(np.float64)).sum(-1) / np.sqrt(8.0)
+    np.testing.assert_allclose(lse, z, rtol=0, atol=1e-14)
+
+
+def test_fwd_blocks_matches_full_forward(oracle):
+    c = shape_ns(2, 2, 16, 16, 4, 4, 8, 3)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 17)
+    idx = oracle.select(s, q, k)
+    out, lse = oracle.fwd(s, q, k, v, idx)
+    pairs = np.array([[0, 0], [3, 5], [1, 15], [3, 2]])
+    o_s, l_s = oracle.fwd_blocks(s, q, k, v, idx, pairs)
+    ot = to_tiles(out, c).reshape(4, 16, 16, 8)
+    lt = to_tiles(lse[..., None], c).reshape(4, 16, 16)
+    for w, (g, i) in enumerate(pairs):
+        assert np.array_equal(o_s[w], ot[g, i]) and np.array_equal(l_s[w], lt[g, i])
+
+
+# --------------------------------------------------------------------------
+# backward with the selection held fixed (Appendix, kernel design paragraph)
+# --------------------------------------------------------------------------
+def _torch_sparse_loss(q, k, v, dout, idx, c):
+    """sum(O * dO) of the block-sparse attention, built from torch fp64 ops on
+    reshape-gathered tiles; autograd supplies the reference gradients."""
+    gh, gw = c.grid_h // c.block_h, c.grid_w // c.block_w
+
+    def tiles(x):
+        B, h, N, D = x.shape
+        t = x.reshape(B, h, gh, c.block_h, gw, c.block_w, D).permute(0, 1, 2, 4, 3, 5, 6)
+        return t.reshape(B, h, gh * gw, c.block_tokens, D)
+
+    qt, kt, vt, dt = tiles(q), tiles(k), tiles(v), tiles(dout)
+    loss = 0.0
+    for e in range(c.batch):
+        for a in range(c.heads):
+            for i in range(c.n_blocks):
+                blocks = [i] + idx[e, a, i].tolist()
+                kk = torch.cat([kt[e, a, j] for j in blocks])
+                vv = torch.cat([vt[e, a, j] for j in blocks])
+                p = torch.softmax(qt[e, a, i] @ kk.T / np.sqrt(c.head_dim), dim=-1)
+                loss = loss + ((p @ vv) * dt[e, a, i]).sum()
+    return loss
+
+
+@pytest.mark.parametrize("n_select", [2, 5])       # 5 = m - 1: dense gradient
+def test_bwd_matches_autograd_of_gathered_attention(oracle, n_select):
+    c = shape_ns(1, 2, 6, 8, 3, 2, 8, n_select)    # m = 8, b = 6
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 18)
+    dout = rand_qkv(c, 19)[0]
+    idx = random_selection(c, 20)
+    dq, dk, dv = oracle.bwd(s, q, k, v, dout, idx)
+    tq, tk, tv = (torch.from_numpy(x).double().requires_grad_() for x in (q, k, v))
+    _torch_sparse_loss(tq, tk, tv, torch.from_numpy(dout).double(), idx, c).backward()
+    np.testing.assert_allclose(dq, tq.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dk, tk.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=0, atol=1e-12)
+
+
+def test_bwd_matches_central_differences_of_the_oracle_forward(oracle):
+    c = shape_ns(1, 1, 4, 8, 2, 2, 4, 2)
+    s = oracle.shape_of(c)
+    rng = np.random.default_rng(21)
+    # values on a 2^-6 grid so that x +- 2^-9 is exact in fp32
+    q, k, v, dout = ((rng.integers(-96, 97, size=(1, 1, 32, 4)) / 64).astype(np.float32)
+                     for _ in range(4))
+    idx = random_selection(c, 22)
+    dq, dk, dv = oracle.bwd(s, q, k, v, dout, idx)
+    hstep = 2.0 ** -9
+
+    def loss(qq, kk, vv):
+        return float((oracle.fwd(s, qq, kk, vv, idx)[0] * dout).sum())
+
+    for name, grad in (("q", dq), ("k", dk), ("v", dv)):
+        for pos in [(0, 0, 0, 0), (0, 0, 13, 2), (0, 0, 31, 3), (0, 0, 6, 1)]:
+            args = {"q": q.copy(), "k": k.copy(), "v": v.copy()}
+            args[name][pos] += hstep
+            up = loss(args["q"], args["k"], args["v"])
+            args[name][pos] -= 2 * hstep
+            dn = loss(args["q"], args["k"], args["v"])
+            fd = (up - dn) / (2 * hstep)
+            assert abs(fd - grad[pos]) <= 1e-5 * max(1.0, abs(fd)), (name, pos)
+
+
+def test_softmax_jacobian_rows_vanish(oracle):
+    """sum_t dS_lt = 0 for every query row, hence sum_t dK_t = 0: adding one
+    vector to every key changes no attention weight."""
+    c = shape_ns(1, 1, 8, 16, 4, 4, 8, 3)      # m = 8, sparse
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 23)
+    dout = rand_qkv(c, 24)[0]
+    idx = oracle.select(s, q, k)
+    dq, dk, dv = oracle.bwd(s, q, k, v, dout, idx)
+    np.testing.assert_allclose(dk.sum(axis=2), 0.0, rtol=0, atol=1e-12)
+    # dV is P^T dO: column sums of P are recovered with dO = 1
+    ones = np.ones_like(dout)
+    _, _, dv1 = oracle.bwd(s, q, k, v, ones, idx)
+    np.testing.assert_allclose(dv1.sum(axis=2), c.n_tokens, rtol=0, atol=1e-10)
