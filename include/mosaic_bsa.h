@@ -1,0 +1,145 @@
+/*
+ * mosaic_bsa.h -- C ABI of the MI355X (gfx950) block-sparse attention library.
+ *
+ * The library implements the hot path of the paper's Block-Sparse Attention
+ * (Section "Mosaic", subsection "Block-Sparse Attention") on a row-major
+ * lat-lon grid:
+ *
+ *   - N = H*W tokens are partitioned into m = N/b non-overlapping blocks
+ *     (Compression paragraph).  A block is a block_h x block_w tile of the
+ *     grid, b = block_h*block_w.  Token t = r*W + c lies in block
+ *     beta = (r / block_h)*(W / block_w) + (c / block_w); inside a block,
+ *     tokens are ordered row-major, tau = (r % block_h)*block_w + (c % block_w).
+ *   - mosaic_bsa_select: mean-pools Q and K per block (pooling equation,
+ *     phi = mean), scores every pair of blocks with the pooled dot product
+ *     (block-level attention equation; its softmax and 1/sqrt(d_k) are
+ *     monotone per row, so they do not change the ranking and are skipped)
+ *     and keeps the top-n key blocks of every query block (Selection
+ *     paragraph).
+ *   - mosaic_bsa_fwd: every token of query block i attends, in one softmax,
+ *     to all tokens of block i (Local Attention paragraph) and of the n
+ *     selected blocks (fine-grained attention equation).
+ *   - mosaic_bsa_bwd: gradients of that attention with the selection held
+ *     fixed (Appendix "Block-sparse attention implementation", kernel design).
+ *
+ * Conventions common to all entry points
+ *   Pointers  q, k, v, out, dout, dq, dk, dv, sel_idx, lse and the workspace
+ *             are DEVICE pointers; `params` is a HOST pointer.  The caller
+ *             owns every buffer; the library never allocates, frees or keeps
+ *             device memory and never synchronises.  All work is enqueued on
+ *             `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *             stream); buffers must stay valid until that work has finished.
+ *   Layout    q, k, v, out, dout, dq, dk, dv: [batch, heads, N, head_dim]
+ *             contiguous, head_dim fastest, element type given by
+ *             params->dtype, base pointers 16-byte aligned.
+ *             sel_idx: int32 [batch, heads, m, n_select].
+ *             lse: fp32 [batch, heads, N], natural-log sum of
+ *             exp(softmax_scale * q.k) over the attended keys.
+ *   Errors    0 on success, a negative MOSAIC_BSA_ERR_* code otherwise.  All
+ *             argument checks run on the host before anything is enqueued;
+ *             on error nothing has been launched.  Inputs must be finite.
+ */
+#ifndef MOSAIC_BSA_H
+#define MOSAIC_BSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOSAIC_BSA_OK = 0,
+    MOSAIC_BSA_ERR_NULL = -1,      /* a required pointer is NULL */
+    MOSAIC_BSA_ERR_SHAPE = -2,     /* non-positive size, or tile does not divide grid */
+    MOSAIC_BSA_ERR_NSELECT = -3,   /* n_select < 0 or n_select > m - 1 */
+    MOSAIC_BSA_ERR_HEAD_DIM = -4,  /* head_dim not in {32, 64, 128} */
+    MOSAIC_BSA_ERR_DTYPE = -5,     /* dtype not MOSAIC_BSA_F32 / MOSAIC_BSA_BF16 */
+    MOSAIC_BSA_ERR_WORKSPACE = -6, /* workspace missing or too small */
+    MOSAIC_BSA_ERR_ALIGN = -7,     /* a tensor base pointer is not 16-byte aligned */
+    MOSAIC_BSA_ERR_LAUNCH = -8,    /* HIP refused a launch (see hipGetLastError) */
+    MOSAIC_BSA_ERR_OP = -9         /* unknown op for mosaic_bsa_workspace_bytes */
+};
+
+enum { MOSAIC_BSA_F32 = 0, MOSAIC_BSA_BF16 = 1 };
+enum { MOSAIC_BSA_OP_SELECT = 0, MOSAIC_BSA_OP_FWD = 1, MOSAIC_BSA_OP_BWD = 2 };
+
+/* Statement of the problem, in the paper's terms. */
+typedef struct {
+    int32_t batch;          /* B */
+    int32_t heads;          /* query heads == key/value heads */
+    int32_t grid_h, grid_w; /* H, W: lat-lon grid, N = H*W tokens */
+    int32_t block_h, block_w; /* tile shape; must divide H and W; b <= 1024 */
+    int32_t head_dim;       /* d_k, one of 32, 64, 128 */
+    int32_t n_select;       /* n selected blocks per query block, 0 <= n <= m-1 */
+    int32_t dtype;          /* element type of q/k/v/out/...: MOSAIC_BSA_F32 or _BF16;
+                               accumulation and softmax are fp32 in both cases */
+    float softmax_scale;    /* <= 0 selects 1/sqrt(head_dim) (fine-grained
+                               attention equation) */
+} mosaic_bsa_params;
+
+/* Bytes of device workspace that `op` needs for `params`; 0 if none.
+ * Returns 0 as well when params is invalid (the op itself reports why). */
+size_t mosaic_bsa_workspace_bytes(const mosaic_bsa_params *params, int op);
+
+/*
+ * Block selection (pooling equation, block-level attention equation,
+ * Selection paragraph).
+ *   q, k      in   device, [B, heads, N, D]
+ *   sel_idx   out  device, int32 [B, heads, m, n]: for every query block the
+ *                  n key blocks j != i with the largest pooled score, ordered
+ *                  by (score descending, block index ascending).
+ *   workspace      device scratch of mosaic_bsa_workspace_bytes(.., OP_SELECT)
+ *                  bytes; on return it holds the pooled q then the pooled k,
+ *                  fp32 [B, heads, m, D] each.
+ * Arithmetic is fixed so that indices are reproducible bit for bit: pooled
+ * sums are fp32 adds in in-tile row-major order followed by one multiply by
+ * 1/b; a score is the fp32 chain acc = fma(qbar[d], kbar[d], acc), d ascending.
+ * n_select == 0 is valid and writes nothing.
+ */
+int mosaic_bsa_select(const mosaic_bsa_params *params, const void *q, const void *k,
+                      int32_t *sel_idx, void *workspace, size_t workspace_bytes,
+                      void *hip_stream);
+
+/*
+ * Block-sparse attention forward (fine-grained attention equation over the
+ * union of the query block itself and its selected blocks, one softmax).
+ *   q, k, v   in   device, [B, heads, N, D]
+ *   sel_idx   in   device, int32 [B, heads, m, n]; every entry in [0, m),
+ *                  no duplicates within a row, never the row's own block;
+ *                  any order.  Entries are trusted: an out-of-range index is
+ *                  undefined behaviour.
+ *   out       out  device, [B, heads, N, D], same element type as q; must not
+ *                  alias an input.
+ *   lse       out  device, fp32 [B, heads, N]; may be NULL.
+ *   workspace      unused by this op (may be NULL with workspace_bytes 0).
+ */
+int mosaic_bsa_fwd(const mosaic_bsa_params *params, const void *q, const void *k,
+                   const void *v, const int32_t *sel_idx, void *out, float *lse,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward of mosaic_bsa_fwd with sel_idx held fixed (no gradient flows
+ * through the top-n choice).
+ *   q, k, v, out, dout  in   device, [B, heads, N, D]
+ *   lse                 in   device, fp32 [B, heads, N] as written by fwd
+ *   sel_idx             in   device, same contract as in mosaic_bsa_fwd
+ *   dq, dk, dv          out  device, [B, heads, N, D], element type of q
+ *   workspace                device scratch of
+ *                            mosaic_bsa_workspace_bytes(.., OP_BWD) bytes.
+ * dk/dv of a key block are reduced over the query blocks that attend to it in
+ * a fixed order (no floating-point atomics): results are run-to-run identical.
+ */
+int mosaic_bsa_bwd(const mosaic_bsa_params *params, const void *q, const void *k,
+                   const void *v, const void *out, const float *lse, const void *dout,
+                   const int32_t *sel_idx, void *dq, void *dk, void *dv,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static, human-readable text for a return code. */
+const char *mosaic_bsa_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOSAIC_BSA_H */

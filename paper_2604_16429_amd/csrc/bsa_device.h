@@ -1,0 +1,66 @@
+// Device-side helpers shared by the HIP kernels of the block-sparse attention
+// library (gfx950 only).  Notation follows the paper: N tokens on an H x W grid,
+// blocks of b = bh*bw tokens, m = N/b blocks, n selected blocks, head dim D.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bsa {
+
+// Geometry of one call, passed by value to every kernel.
+struct Geom {
+    int32_t heads;        // h
+    int32_t grid_w;       // W
+    int32_t block_h;      // bh
+    int32_t block_w;      // bw
+    int32_t blocks_per_row;  // W / bw
+    int32_t n_blocks;     // m
+    int32_t block_tokens; // b
+    int32_t n_select;     // n
+    int64_t n_tokens;     // N
+    float   scale;        // softmax scale
+};
+
+// Token index (inside one [N, D] slice) of in-tile position tau of block beta:
+// the tile partition of the grid (Compression paragraph, with tiles as blocks).
+__device__ __forceinline__ int64_t token_of(const Geom& g, int beta, int tau)
+{
+    const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
+    const int rr = tau / g.block_w, cc = tau - rr * g.block_w;
+    return (int64_t)(br * g.block_h + rr) * g.grid_w + (bc * g.block_w + cc);
+}
+
+// bf16 <-> fp32 on raw bit patterns
+__device__ __forceinline__ float bf16_to_f32(uint16_t b)
+{
+    return __uint_as_float((uint32_t)b << 16);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)   // round to nearest even
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Element loaders: 4 consecutive channels as fp32.
+__device__ __forceinline__ float4 load4(const float* p) { return *(const float4*)p; }
+__device__ __forceinline__ float4 load4(const uint16_t* p)
+{
+    const uint2 r = *(const uint2*)p;
+    return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
+                       __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
+}
+
+__device__ __forceinline__ void store4(float* p, float4 v) { *(float4*)p = v; }
+__device__ __forceinline__ void store4(uint16_t* p, float4 v)
+{
+    uint2 r;
+    r.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+    r.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    *(uint2*)p = r;
+}
+
+}  // namespace bsa

@@ -1,0 +1,26 @@
+// Host-side launch entry points of the individual kernels; called only by the
+// C-ABI layer after it has validated the arguments.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bsa_device.h"
+
+namespace bsa {
+
+// Query blocks ranked per workgroup by the selection kernel; 0 = m too large.
+int select_group_size(int m, int D);
+
+hipError_t launch_pool(bool is_bf16, const void* q, const void* k, float* qbar, float* kbar,
+                       const Geom& g, int D, int64_t BH, hipStream_t stream);
+
+hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, const Geom& g,
+                         int D, int64_t BH, hipStream_t stream);
+
+// Any tile shape / head dim in {32, 64, 128} / dtype; fp32 vector arithmetic.
+hipError_t launch_fwd_generic(bool is_bf16, const void* q, const void* k, const void* v,
+                              const int32_t* sel_idx, void* out, float* lse, const Geom& g, int D,
+                              int64_t BH, hipStream_t stream);
+
+}  // namespace bsa

@@ -1,0 +1,272 @@
+// Block selection for block-sparse attention on gfx950:
+//   pool_kernel    mean-pooled block representations of Q and K (pooling
+//                  equation, phi = mean);
+//   select_kernel  block-level scores (block-level attention equation, in its
+//                  rank-equivalent raw dot-product form) and the top-n key
+//                  blocks of every query block (Selection paragraph).
+//
+// The arithmetic is pinned so that the emitted indices are reproducible bit
+// for bit by a scalar loop: pooled sums are fp32 adds in in-tile row-major
+// order followed by one multiply by 1/b; a score is the fp32 chain
+// acc = fma(qbar[d], kbar[d], acc) for d ascending from +0; candidates are
+// ranked by (score descending, block index ascending) and the query block
+// itself is never a candidate.  MFMA is deliberately not used here: its
+// internal accumulation order cannot be reproduced by such a loop.
+#include "bsa_device.h"
+#include "bsa_launch.h"
+
+namespace bsa {
+
+// ---------------------------------------------------------------------------
+// pooling
+// ---------------------------------------------------------------------------
+// One workgroup per (tensor, batch*head, row of tiles).  A work item is (tile
+// in that row, group of VEC channels); it walks the tile's tokens in in-tile
+// row-major order, which is the pinned summation order.  Consecutive lanes
+// take consecutive channel groups, so every load covers whole 128-byte lines
+// and each tile row (bw*D elements, contiguous in memory) is consumed by
+// consecutive iterations.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
+                                                   const T* __restrict__ k,
+                                                   float* __restrict__ qbar,
+                                                   float* __restrict__ kbar, Geom g, int D,
+                                                   int64_t BH)
+{
+    // blockIdx.x = (tensor * BH + batch*head) * tile_rows + tile_row
+    const int tile_rows = g.n_blocks / g.blocks_per_row;
+    const int tile_row = blockIdx.x % tile_rows;
+    int64_t bh_idx = blockIdx.x / tile_rows;     // tensor * BH + batch*head
+    const bool is_k = bh_idx >= BH;
+    if (is_k) bh_idx -= BH;
+    const T* __restrict__ x = is_k ? k : q;
+    float* __restrict__ xbar = is_k ? kbar : qbar;
+    const int groups = D / VEC;
+    const int items = g.blocks_per_row * groups;
+    const float inv_b = 1.0f / (float)g.block_tokens;
+    x += bh_idx * g.n_tokens * D;
+
+    for (int item = threadIdx.x; item < items; item += blockDim.x) {
+        const int tile_col = item / groups;
+        const int ch = (item - tile_col * groups) * VEC;
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+        for (int rr = 0; rr < g.block_h; ++rr) {
+            const T* row = x + ((int64_t)(tile_row * g.block_h + rr) * g.grid_w +
+                                (int64_t)tile_col * g.block_w) * D + ch;
+#pragma unroll 8
+            for (int cc = 0; cc < g.block_w; ++cc) {
+#pragma unroll
+                for (int e4 = 0; e4 < VEC; e4 += 4) {
+                    const float4 v = load4(row + (int64_t)cc * D + e4);
+                    acc[e4 + 0] = acc[e4 + 0] + v.x;
+                    acc[e4 + 1] = acc[e4 + 1] + v.y;
+                    acc[e4 + 2] = acc[e4 + 2] + v.z;
+                    acc[e4 + 3] = acc[e4 + 3] + v.w;
+                }
+            }
+        }
+        const int beta = tile_row * g.blocks_per_row + tile_col;
+        float* dst = xbar + (bh_idx * g.n_blocks + beta) * D + ch;
+#pragma unroll
+        for (int e4 = 0; e4 < VEC; e4 += 4)
+            store4(dst + e4, make_float4(acc[e4] * inv_b, acc[e4 + 1] * inv_b,
+                                         acc[e4 + 2] * inv_b, acc[e4 + 3] * inv_b));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// scores + top-n
+// ---------------------------------------------------------------------------
+// Order-preserving map fp32 -> u32 (larger float <=> larger integer).  Every
+// non-NaN input maps to a value >= 0x007fffff; the clamp keeps even a NaN bit
+// pattern away from 0, which marks "removed".
+__device__ __forceinline__ uint32_t rank_key(float s)
+{
+    const uint32_t u = __float_as_uint(s + 0.0f);    // -0 -> +0
+    return max((u & 0x80000000u) ? ~u : (u | 0x80000000u), 1u);
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+
+// Wave-wide reductions over all 64 lanes (all lanes must be active); the
+// result is wave-uniform.  Four DPP butterfly steps inside each row of 16
+// lanes, then the four row results are combined through scalar registers.
+__device__ __forceinline__ uint32_t wave_umax(uint32_t v)
+{
+    v = max(v, dpp<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = max(v, dpp<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = max(v, dpp<0x141>(v));   // row_half_mirror
+    v = max(v, dpp<0x140>(v));   // row_mirror
+    const uint32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    const uint32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return max(max(a, b), max(c, d));
+}
+
+__device__ __forceinline__ uint32_t wave_umin(uint32_t v)
+{
+    v = min(v, dpp<0xB1>(v));
+    v = min(v, dpp<0x4E>(v));
+    v = min(v, dpp<0x141>(v));
+    v = min(v, dpp<0x140>(v));
+    const uint32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    const uint32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return min(min(a, b), min(c, d));
+}
+
+// One workgroup of 256 threads ranks G consecutive query blocks of one
+// (batch, head).
+//   phase 1: thread t owns key block j = chunk*256 + t, holds kbar_j in
+//            registers and runs the pinned fma chain against each of the G
+//            pooled queries (read from LDS as wave-wide broadcasts); the
+//            ranking keys of all m candidates of each query land in LDS.
+//   phase 2: one wavefront per query block extracts the n best candidates by
+//            repeated arg-max: every lane caches the best of the candidates
+//            j == lane (mod 64); a wave-wide max of the scores and then a
+//            wave-wide min of the indices among the lanes holding that max
+//            give the next selected block; only the winner's lane rescans.
+// LDS: G*D floats (pooled queries) + G*m u32 (ranking keys).
+template <int D>
+__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ qbar,
+                                                     const float* __restrict__ kbar,
+                                                     int32_t* __restrict__ sel_idx, Geom g,
+                                                     int G)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* q_s = (float*)smem;                       // [G][D]
+    uint32_t* key_s = (uint32_t*)(q_s + G * D);      // [G][m]
+
+    const int m = g.n_blocks, n = g.n_select;
+    // blockIdx.x = batch*head * groups + group
+    const int groups = (m + G - 1) / G;
+    const int64_t bh_idx = blockIdx.x / groups;
+    const int i0 = (int)(blockIdx.x - bh_idx * groups) * G;
+    const int rows = min(G, m - i0);
+    qbar += (bh_idx * m + i0) * D;
+    kbar += bh_idx * m * D;
+
+    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) q_s[e] = qbar[e];
+    __syncthreads();
+
+    // ---- phase 1: scores
+    for (int j = threadIdx.x; j < m; j += blockDim.x) {
+        float kr[D];
+        const float4* krow = (const float4*)(kbar + (int64_t)j * D);
+#pragma unroll
+        for (int d4 = 0; d4 < D / 4; ++d4) {
+            const float4 v = krow[d4];
+            kr[4 * d4 + 0] = v.x; kr[4 * d4 + 1] = v.y;
+            kr[4 * d4 + 2] = v.z; kr[4 * d4 + 3] = v.w;
+        }
+        for (int r = 0; r < rows; ++r) {
+            const float4* qrow = (const float4*)(q_s + r * D);
+            float acc = 0.0f;
+#pragma unroll
+            for (int d4 = 0; d4 < D / 4; ++d4) {
+                const float4 qv = qrow[d4];
+                acc = __builtin_fmaf(qv.x, kr[4 * d4 + 0], acc);
+                acc = __builtin_fmaf(qv.y, kr[4 * d4 + 1], acc);
+                acc = __builtin_fmaf(qv.z, kr[4 * d4 + 2], acc);
+                acc = __builtin_fmaf(qv.w, kr[4 * d4 + 3], acc);
+            }
+            key_s[r * m + j] = (j == i0 + r) ? 0u : rank_key(acc);
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: top-n per query block, one wavefront each
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = wave; r < rows; r += (int)(blockDim.x >> 6)) {
+        uint32_t* keys = key_s + r * m;
+        int32_t* dst = sel_idx + ((bh_idx * m) + i0 + r) * n;
+        uint32_t best = 0u, best_j = 0xffffffffu;
+        for (int j = lane; j < m; j += 64) {
+            const uint32_t u = keys[j];
+            if (u > best) { best = u; best_j = (uint32_t)j; }
+        }
+        for (int t = 0; t < n; ++t) {
+            const uint32_t top = wave_umax(best);
+            const uint32_t win = wave_umin(best == top ? best_j : 0xffffffffu);
+            if (lane == 0) dst[t] = (int32_t)win;
+            if ((win & 63u) == (uint32_t)lane) {
+                keys[win] = 0u;
+                best = 0u; best_j = 0xffffffffu;
+                for (int j = lane; j < m; j += 64) {
+                    const uint32_t u = keys[j];
+                    if (u > best) { best = u; best_j = (uint32_t)j; }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host-side launchers
+// ---------------------------------------------------------------------------
+static constexpr size_t kSelectLdsBudget = 144 * 1024;
+
+int select_group_size(int m, int D)
+{
+    // largest G in [1, 8] whose LDS footprint fits; 0 if even G = 1 does not
+    for (int G = 8; G >= 1; G >>= 1)
+        if ((size_t)G * (D + (size_t)m) * 4 <= kSelectLdsBudget) return G;
+    return 0;
+}
+
+template <typename T, int VEC>
+static hipError_t launch_pool_t(const void* q, const void* k, float* qbar, float* kbar,
+                                const Geom& g, int D, int64_t BH, hipStream_t stream)
+{
+    const int tile_rows = g.n_blocks / g.blocks_per_row;
+    const int items = g.blocks_per_row * (D / VEC);
+    const int threads = items >= 256 ? 256 : ((items + 63) / 64) * 64;
+    dim3 grid((unsigned)(2 * BH * tile_rows));
+    hipLaunchKernelGGL((pool_kernel<T, VEC>), grid, dim3(threads), 0, stream, (const T*)q,
+                       (const T*)k, qbar, kbar, g, D, BH);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool(bool is_bf16, const void* q, const void* k, float* qbar, float* kbar,
+                       const Geom& g, int D, int64_t BH, hipStream_t stream)
+{
+    return is_bf16 ? launch_pool_t<uint16_t, 8>(q, k, qbar, kbar, g, D, BH, stream)
+                   : launch_pool_t<float, 4>(q, k, qbar, kbar, g, D, BH, stream);
+}
+
+template <int D>
+static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t* sel_idx,
+                                  const Geom& g, int64_t BH, hipStream_t stream)
+{
+    const int G = select_group_size(g.n_blocks, D);
+    const size_t lds = (size_t)G * (D + (size_t)g.n_blocks) * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)select_kernel<D>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kSelectLdsBudget);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)(BH * ((g.n_blocks + G - 1) / G)));
+    hipLaunchKernelGGL((select_kernel<D>), grid, dim3(256), lds, stream, qbar, kbar, sel_idx, g,
+                       G);
+    return hipGetLastError();
+}
+
+hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, const Geom& g,
+                         int D, int64_t BH, hipStream_t stream)
+{
+    switch (D) {
+    case 32: return launch_select_t<32>(qbar, kbar, sel_idx, g, BH, stream);
+    case 64: return launch_select_t<64>(qbar, kbar, sel_idx, g, BH, stream);
+    case 128: return launch_select_t<128>(qbar, kbar, sel_idx, g, BH, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace bsa

@@ -1,0 +1,57 @@
+"""Runs the HIP library through its C ABI (via the thin Python binding) on
+numpy inputs; used by the GPU parity tests only."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2604_16429_amd as M
+from paper_2604_16429_amd import binding
+
+
+def params_of(cfg, n_select=None, softmax_scale=0.0):
+    return M.Params(cfg.batch, cfg.heads, cfg.grid_h, cfg.grid_w, cfg.block_h,
+                    cfg.block_w, cfg.head_dim,
+                    cfg.n_select if n_select is None else n_select,
+                    binding.BF16 if cfg.dtype == "bf16" else binding.F32,
+                    softmax_scale)
+
+
+def to_dev(x, cfg):
+    """fp32 numpy (bf16-representable when cfg is bf16) -> device tensor."""
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
+    return t.to(torch.bfloat16) if cfg.dtype == "bf16" else t
+
+
+def select_dev(cfg, q_d, k_d, n_select=None):
+    p = params_of(cfg, n_select)
+    n = p.n_select
+    idx = torch.full((cfg.batch, cfg.heads, p.n_blocks, n), -1, dtype=torch.int32,
+                     device="cuda")
+    ws = torch.empty(max(M.mosaic_bsa_workspace_bytes(p, binding.OP_SELECT), 256),
+                     dtype=torch.uint8, device="cuda")
+    M.mosaic_bsa_select(p, q_d, k_d, idx, ws)
+    return idx
+
+
+def fwd_dev(cfg, q_d, k_d, v_d, idx_d, n_select=None, softmax_scale=0.0, want_lse=True):
+    p = params_of(cfg, n_select, softmax_scale)
+    out = torch.full_like(q_d, float("nan"))
+    lse = (torch.full((cfg.batch, cfg.heads, p.n_tokens), float("nan"),
+                      dtype=torch.float32, device="cuda") if want_lse else None)
+    M.mosaic_bsa_fwd(p, q_d, k_d, v_d, idx_d, out, lse)
+    return out, lse
+
+
+def gpu_select(cfg, q, k, n_select=None):
+    idx = select_dev(cfg, to_dev(q, cfg), to_dev(k, cfg), n_select)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy()
+
+
+def gpu_fwd(cfg, q, k, v, idx, n_select=None, softmax_scale=0.0):
+    idx_d = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).to("cuda")
+    out, lse = fwd_dev(cfg, to_dev(q, cfg), to_dev(k, cfg), to_dev(v, cfg), idx_d,
+                       n_select, softmax_scale)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), lse.cpu().numpy()

@@ -1,0 +1,158 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on the same seeded inputs.
+
+Bars: selected indices bit-exact (element for element, in the emitted order);
+outputs within 1e-5 of max|O| in fp32 mode and within 2e-2 max-abs in bf16
+mode; lse within 1e-3 (bf16) / 1e-5 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+from inputs.fields import get_config, make_problem, round_to_bf16
+from tests.helpers import rand_qkv, random_selection, shape_ns, to_tiles
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_util
+    return gpu_util
+
+
+def check_out(cfg, out_gpu, lse_gpu, out_ref, lse_ref):
+    if cfg.dtype == "bf16":
+        err = np.abs(out_gpu - out_ref).max()
+        assert err <= 2e-2, f"bf16 max-abs error {err}"
+        assert np.abs(lse_gpu - lse_ref).max() <= 1e-3
+    else:
+        rel = np.abs(out_gpu - out_ref).max() / max(np.abs(out_ref).max(), 1e-30)
+        assert rel <= 1e-5, f"fp32 relative error {rel}"
+        assert np.abs(lse_gpu - lse_ref).max() <= 1e-5 * max(1.0, np.abs(lse_ref).max())
+
+
+def full_parity(G, oracle, cfg, q, k, v):
+    s = oracle.shape_of(cfg)
+    idx_ref = oracle.select(s, q, k)
+    idx_gpu = G.gpu_select(cfg, q, k)
+    assert np.array_equal(idx_gpu, idx_ref)
+    out_ref, lse_ref = oracle.fwd(s, q, k, v, idx_ref)
+    out_gpu, lse_gpu = G.gpu_fwd(cfg, q, k, v, idx_gpu)
+    check_out(cfg, out_gpu, lse_gpu, out_ref, lse_ref)
+
+
+def test_config1_tiny_grid_fp32(G, oracle):
+    p = make_problem(1)
+    full_parity(G, oracle, p.cfg, p.q, p.k, p.v)
+
+
+def test_config2_global_grid_bf16(G, oracle):
+    p = make_problem(2)
+    full_parity(G, oracle, p.cfg, p.q, p.k, p.v)
+
+
+def test_config3_ensemble_reduced_batch(G, oracle):
+    p = make_problem(3, batch=2, heads=2)
+    full_parity(G, oracle, p.cfg, p.q, p.k, p.v)
+
+
+def test_config5_forward_reduced_batch(G, oracle):
+    p = make_problem(5, batch=1, heads=2)
+    full_parity(G, oracle, p.cfg, p.q, p.k, p.v)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("H,W,bh,bw,D,n", [
+    (12, 18, 6, 6, 32, 3),      # b = 36: ragged against the 64-row chunk
+    (16, 48, 8, 12, 64, 5),     # b = 96: one full chunk + a tail
+    (8, 8, 8, 8, 64, 0),        # a single block, nothing to select
+    (32, 64, 32, 32, 32, 1),    # b = 1024, the largest tile
+    (16, 16, 2, 2, 128, 63),    # every block selected: dense attention
+    (24, 40, 8, 8, 128, 7),
+])
+def test_edge_shapes(G, oracle, dtype, H, W, bh, bw, D, n):
+    cfg = shape_ns(2, 3, H, W, bh, bw, D, n, dtype)
+    q, k, v = rand_qkv(cfg, 100 + H + W)
+    if dtype == "bf16":
+        q, k, v = round_to_bf16(q), round_to_bf16(k), round_to_bf16(v)
+    full_parity(G, oracle, cfg, q, k, v)
+
+
+def test_ties_and_exact_arithmetic_selection(G, oracle):
+    """Constant keys (all scores tie) and quantised data (exact arithmetic):
+    the tie-break and the never-select-yourself rule must match bit for bit."""
+    cfg = shape_ns(1, 2, 32, 64, 8, 8, 32, 6, "fp32")
+    s = oracle.shape_of(cfg)
+    q, _, _ = rand_qkv(cfg, 7)
+    k = np.ones_like(q)
+    idx = G.gpu_select(cfg, q, k)
+    assert np.array_equal(idx, oracle.select(s, q, k))
+    for i in range(cfg.n_blocks):
+        assert idx[0, 0, i].tolist() == [j for j in range(cfg.n_blocks) if j != i][:6]
+    rng = np.random.default_rng(8)
+    qq = (rng.integers(-8, 9, size=q.shape) / 4).astype(np.float32)
+    kq = (rng.integers(-2, 3, size=q.shape) / 4).astype(np.float32)   # many ties
+    assert np.array_equal(G.gpu_select(cfg, qq, kq), oracle.select(s, qq, kq))
+
+
+def test_pooled_means_in_workspace_are_bit_exact(G, oracle):
+    import paper_2604_16429_amd as M
+    from paper_2604_16429_amd import binding
+    p = make_problem(2)
+    cfg = p.cfg
+    s = oracle.shape_of(cfg)
+    prm = G.params_of(cfg)
+    q_d, k_d = G.to_dev(p.q, cfg), G.to_dev(p.k, cfg)
+    nbytes = M.mosaic_bsa_workspace_bytes(prm, binding.OP_SELECT)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    idx = torch.empty((cfg.batch, cfg.heads, cfg.n_blocks, cfg.n_select), dtype=torch.int32,
+                      device="cuda")
+    M.mosaic_bsa_select(prm, q_d, k_d, idx, ws)
+    torch.cuda.synchronize()
+    cnt = cfg.batch * cfg.heads * cfg.n_blocks * cfg.head_dim
+    wsf = ws.view(torch.float32).cpu().numpy()
+    assert np.array_equal(wsf[:cnt].reshape(oracle.pool(s, p.q).shape), oracle.pool(s, p.q))
+    half = nbytes // 8
+    assert np.array_equal(wsf[half:half + cnt].reshape(-1), oracle.pool(s, p.k).reshape(-1))
+
+
+def test_forward_properties_on_gpu(G, oracle):
+    cfg = get_config(2, heads=2)
+    p = make_problem(2, heads=2)
+    s = oracle.shape_of(cfg)
+    idx = oracle.select(s, p.q, p.k)
+    out, lse = G.gpu_fwd(cfg, p.q, p.k, p.v, idx)
+    # deterministic: bitwise equal reruns
+    out2, lse2 = G.gpu_fwd(cfg, p.q, p.k, p.v, idx)
+    assert np.array_equal(out, out2) and np.array_equal(lse, lse2)
+    # rows of the attention matrix sum to one: constant V comes back
+    const = round_to_bf16(np.linspace(-1, 1, 64).astype(np.float32))
+    outc, _ = G.gpu_fwd(cfg, p.q, p.k, np.broadcast_to(const, p.v.shape).copy(), idx)
+    assert np.abs(outc - const).max() <= 1e-2
+    # order of the selected blocks does not matter (up to rounding)
+    rng = np.random.default_rng(3)
+    perm = np.stack([rng.permutation(cfg.n_select) for _ in range(cfg.n_blocks)])
+    idx_p = np.take_along_axis(idx, np.broadcast_to(perm, idx.shape), axis=3)
+    outp, lsep = G.gpu_fwd(cfg, p.q, p.k, p.v, idx_p)
+    assert np.abs(outp - out).max() <= 2e-2 and np.abs(lsep - lse).max() <= 1e-3
+    # blocks that query block i did not select cannot influence its rows
+    i = 77
+    untouched = [j for j in range(cfg.n_blocks) if j != i and j not in idx[0, 0, i]]
+    kt, vt = to_tiles(p.k, cfg).copy(), to_tiles(p.v, cfg).copy()
+    kt[0, 0, untouched] = 3.0
+    vt[0, 0, untouched] = -2.0
+    from tests.helpers import from_tiles
+    out3, _ = G.gpu_fwd(cfg, p.q, from_tiles(kt, cfg), from_tiles(vt, cfg), idx)
+    assert np.array_equal(to_tiles(out, cfg)[0, 0, i], to_tiles(out3, cfg)[0, 0, i])
+
+
+def test_arbitrary_selection_and_explicit_scale(G, oracle):
+    cfg = shape_ns(1, 2, 32, 48, 8, 8, 64, 6, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 11))
+    s = oracle.shape_of(cfg)
+    idx = random_selection(cfg, 12)
+    out_ref, lse_ref = oracle.fwd(s, q, k, v, idx, scale=0.2)
+    out, lse = G.gpu_fwd(cfg, q, k, v, idx, softmax_scale=0.2)
+    check_out(cfg, out, lse, out_ref, lse_ref)
