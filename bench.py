@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse attention hot path on one MI355X.
+
+One "step" is one pass of the whole hot path -- block selection (pooling,
+block scores, top-n) followed by the block-sparse attention forward -- over
+one batch of seeded synthetic grid fields that already reside in HBM.
+
+Default workload: the 1.5 degree global grid (120 x 240 = 28,800 tokens) with a
+24-member ensemble batch, 16 heads, head dim 64, 8 x 8 tiles and the 16 best
+blocks per query block, bf16 I/O with fp32 accumulation.
+
+Prints ONE JSON line: tokens/s of the whole step as `value`, effective
+TFLOP/s of the dense block products, the roofline of the dominant kernel (the
+attention forward, MFMA-bound) from HIP-event timings taken inside the timed
+region, and the CPU oracle timed on a bounded sample on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per forward launch measured with rocprofv3 --pmc (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by the same counter on a plain copy kernel); see the
+# summaries under profiles/.  None until measured for a workload.
+MEASURED_FWD_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="configuration id (1-5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(problem, cfg):
+    """The oracle, as it stands, on the host cores: the first batch entries
+    (all heads) of the same workload through select + forward."""
+    import dataclasses
+    from oracle import bsa_oracle
+    nb = min(cfg.batch, 8)
+    sub = dataclasses.replace(cfg, batch=nb)
+    s = bsa_oracle.shape_of(sub)
+    q, k, v = problem.q[:nb], problem.k[:nb], problem.v[:nb]
+    t0 = time.perf_counter()
+    idx = bsa_oracle.select(s, q, k)
+    t1 = time.perf_counter()
+    bsa_oracle.fwd(s, q, k, v, idx)
+    t2 = time.perf_counter()
+    return {
+        "value": nb * cfg.n_tokens / (t2 - t0), "unit": "tokens/s",
+        "cores": bsa_oracle.threads(), "kind": "oracle",
+        "sample": (f"batch entries 0..{nb - 1} of the workload, all {cfg.heads} heads "
+                   f"({nb * cfg.n_tokens} tokens): select {t1 - t0:.2f} s + forward "
+                   f"{t2 - t1:.2f} s, double-precision attention"),
+        "seconds": t2 - t0,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path "
+              "(batch and heads shard without any exchange); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_16429_amd as M
+    from paper_2604_16429_amd import binding
+    from inputs.fields import get_config, make_problem
+
+    cfg = get_config(args.config)
+    problem = make_problem(args.config)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    is_bf16 = cfg.dtype == "bf16"
+
+    def up(x):
+        t = torch.from_numpy(x).to(dev)
+        return t.to(torch.bfloat16) if is_bf16 else t
+
+    q, k, v = up(problem.q), up(problem.k), up(problem.v)
+    prm = M.Params(cfg.batch, cfg.heads, cfg.grid_h, cfg.grid_w, cfg.block_h, cfg.block_w,
+                   cfg.head_dim, cfg.n_select, binding.BF16 if is_bf16 else binding.F32, 0.0)
+    idx = torch.empty((cfg.batch, cfg.heads, cfg.n_blocks, cfg.n_select), dtype=torch.int32,
+                      device=dev)
+    out = torch.empty_like(q)
+    lse = torch.empty((cfg.batch, cfg.heads, cfg.n_tokens), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(M.mosaic_bsa_workspace_bytes(prm, binding.OP_SELECT), 256),
+                     dtype=torch.uint8, device=dev)
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        M.mosaic_bsa_select(prm, q, k, idx, ws)
+        if events is not None:
+            events[1].record()
+        M.mosaic_bsa_fwd(prm, q, k, v, idx, out, lse)
+        if events is not None:
+            events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    sel_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    fwd_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    tokens = cfg.batch * cfg.n_tokens
+    flops = cfg.fwd_flops()
+    eff_tflops = flops / (fwd_ms * 1e-3) / 1e12
+    esz = 2 if is_bf16 else 4
+    compulsory = 4 * cfg.batch * cfg.heads * cfg.n_tokens * cfg.head_dim * esz
+    traffic = MEASURED_FWD_TRAFFIC_BYTES.get(args.config)
+
+    result = {
+        "metric": "block-sparse attn tokens/s @1.5deg grid (select + forward); "
+                  "effective TFLOP/s and % MFMA peak alongside",
+        "value": tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {
+            "workload": (f"config {cfg.config_id}: {cfg.grid_h}x{cfg.grid_w} lat-lon grid "
+                         f"({cfg.n_tokens} tokens), batch {cfg.batch}, {cfg.heads} heads, "
+                         f"head_dim {cfg.head_dim}, tiles {cfg.block_h}x{cfg.block_w}, "
+                         f"local + top-{cfg.n_select} blocks"),
+            "tokens_per_step": tokens,
+        },
+        "select_ms": sel_ms, "fwd_ms": fwd_ms,
+        "effective_tflops": eff_tflops,
+        "pct_mfma_peak": 100.0 * eff_tflops / MFMA_BF16_PEAK_TFLOPS,
+        "fwd_only_tokens_per_s": tokens / (fwd_ms * 1e-3),
+        "compulsory_hbm_gbs": compulsory / (fwd_ms * 1e-3) / 1e9,
+        "roofline": {
+            "kernel": "attention forward",
+            "bound": "mfma", "achieved": eff_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": eff_tflops / MFMA_BF16_PEAK_TFLOPS,
+            "traffic": traffic,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(problem, cfg)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -113,10 +113,12 @@ extern "C" int mosaic_bsa_fwd(const mosaic_bsa_params* params, const void* q, co
         return MOSAIC_BSA_ERR_ALIGN;
 
     hipStream_t stream = (hipStream_t)hip_stream;
-    if (bsa::launch_fwd_generic(c.is_bf16, q, k, v, sel_idx, out, lse, c.g, c.D, c.BH, stream) !=
-        hipSuccess)
-        return MOSAIC_BSA_ERR_LAUNCH;
-    return MOSAIC_BSA_OK;
+    const hipError_t e =
+        bsa::fwd_mfma_supported(c.is_bf16, c.g, c.D)
+            ? bsa::launch_fwd_mfma(q, k, v, sel_idx, out, lse, c.g, c.D, c.BH, stream)
+            : bsa::launch_fwd_generic(c.is_bf16, q, k, v, sel_idx, out, lse, c.g, c.D, c.BH,
+                                      stream);
+    return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
 }
 
 extern "C" int mosaic_bsa_bwd(const mosaic_bsa_params* params, const void* q, const void* k,

@@ -23,4 +23,10 @@ hipError_t launch_fwd_generic(bool is_bf16, const void* q, const void* k, const 
                               const int32_t* sel_idx, void* out, float* lse, const Geom& g, int D,
                               int64_t BH, hipStream_t stream);
 
+// bf16 MFMA forward; covers the shapes fwd_mfma_supported() accepts.
+bool fwd_mfma_supported(bool is_bf16, const Geom& g, int D);
+hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const int32_t* sel_idx,
+                           void* out, float* lse, const Geom& g, int D, int64_t BH,
+                           hipStream_t stream);
+
 }  // namespace bsa
