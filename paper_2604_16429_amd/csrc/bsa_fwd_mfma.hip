@@ -26,10 +26,23 @@
 //     on the global side of the direct-to-LDS load (which lane fetches which
 //     chunk), because that load always writes lanes to consecutive LDS
 //     addresses.
-// The loads of the next K tile are issued as soon as the current K fragments
-// are in registers, and likewise for V, so the gather of pair c+1 overlaps the
-// matrix work of pair c; with two such wavefronts per SIMD one wave's softmax
-// (vector ALU) overlaps the other's MFMAs.
+// Order of work for pair c (K(c) fragments are already in registers):
+//   S^T = K(c) Q^T (16 MFMAs); V(c) fragments are requested from LDS while the
+//   weights P(c) are computed on the vector ALU; once they are in registers the
+//   V(c+1) gather may overwrite the V tile; the K(c+1) fragments are requested
+//   before O^T += V(c)^T P(c)^T (16 MFMAs) so that the next pair starts without
+//   waiting for LDS; then the K(c+2) gather overwrites the K tile.  The matrix
+//   work of a pair thus forms one run (PV of pair c, QK of pair c+1) and the
+//   vector work another; two wavefronts per SIMD overlap one wave's run of
+//   MFMAs with the other's exponentials.
+//
+// Softmax without a row maximum per pair.  m_ref is the reference the
+// exponentials are taken against.  A pair first computes its weights against
+// the current m_ref; only if some row sum of the pair exceeds 2^12 (which
+// covers the first pair, where m_ref = -inf) does the wavefront take the slow
+// path: find the row maxima, move m_ref, rescale O and the normaliser, and
+// recompute the pair's weights.  Any reference gives the same softmax; bounded
+// weights keep fp32 and bf16 far from overflow.
 #include "bsa_device.h"
 #include "bsa_launch.h"
 
@@ -80,12 +93,36 @@ __device__ __forceinline__ void gather_tile(__amdgpu_buffer_rsrc_t rsrc, uint32_
                                                  voff[r], origin_bytes, 0, 0);
 }
 
-// Written with builtins (never inline asm): the compiler must see these reads
-// of MFMA results to place the wait states the hardware requires.
-__device__ __forceinline__ float max3(float a, float b, float c)
+// P^T = exp2(S^T c2 - m_ref) for one query half nt, packed to bf16 B operands;
+// returns this lane's sum of the rounded weights (two per instruction).  Only
+// builtins touch the MFMA results (never inline asm): the compiler must see
+// these reads to place the wait states the hardware requires.
+__device__ __forceinline__ float softmax_weights(const f32x16 (&s)[2][2], int nt, float c2,
+                                                 float neg_m, bf16x8 (&pf)[2][4])
 {
-    return __builtin_fmaxf(__builtin_fmaxf(a, b), c);
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+    float rs = 0.0f;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int h8 = 0; h8 < 2; ++h8) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[mt][nt][8 * h8 + e], c2, neg_m));
+                const float p1 =
+                    __builtin_amdgcn_exp2f(fmaf(s[mt][nt][8 * h8 + e + 1], c2, neg_m));
+                w[e >> 1] = pack_bf16(p0, p1);
+                rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e >> 1]), ones,
+                                                     rs, false);
+            }
+            const uint4 packed = make_uint4(w[0], w[1], w[2], w[3]);
+            pf[nt][2 * mt + h8] = __builtin_bit_cast(bf16x8, packed);
+        }
+    return rs;
 }
+
+constexpr float kSumLimit = 4096.0f;
 
 __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
@@ -127,6 +164,9 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, slice_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t v_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(v + base), 0, slice_bytes, 0x00020000);
+    // zero records: every access is out of range, the load moves nothing
+    const __amdgpu_buffer_rsrc_t null_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, 0, 0x00020000);
 
     // Attended blocks (own block + selection) in ascending block order when
     // they fit one wavefront: query blocks that run at the same time on an XCD
@@ -163,6 +203,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         return (uint32_t)((br * g.block_h * g.grid_w + bc * g.block_w) * (D * 2));
     };
 
+    // K(0) and V(0) go to LDS
     {
         const uint32_t origin_0 = origin_of(block_at(0));
         gather_tile(k_rsrc, origin_0, voff, k_lds);
@@ -195,13 +236,9 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) oacc[a][b] = zero16;
-    // Softmax state per query column (base-2 domain).  m_ref is the reference
-    // maximum the exponentials are taken against; it only follows the running
-    // maximum when that has grown by more than kRescaleGap, so most pairs skip
-    // the rescaling of O.  Weights stay below 2^kRescaleGap.
-    constexpr float kRescaleGap = 8.0f;
+    // Softmax state per query column (base-2 domain): reference maximum and
+    // this lane's share of the normaliser.
     float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
-    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 
     // V (transposing read): source lane s of 16-lane group gq supplies 8 bytes of
     //   V[key0 + 8 rd + 4 h + s/4][dbase + 4 (s%4)], h = gq/2, dbase = 16 (gq%2) + 32 dt
@@ -209,13 +246,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const int v_row_in_step = 4 * (gq >> 1) + (s16 >> 2);
     const int v_col = 16 * (gq & 1) + 4 * (s16 & 3);     // channel (before + 32 dt)
 
-    for (int c = 0; c <= n; ++c) {
-        const uint32_t origin_next = origin_of((c < n) ? block_at(c + 1) : 0);
-
-        // ---- K(c) has landed (loads complete in order: all but the 8 most
-        // recent -- the V(c) gather -- are done): K fragments -> registers
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        bf16x8 kf[2][4];
+    auto read_k_frags = [&](bf16x8 (&kf)[2][4]) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -223,10 +254,18 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
                 const int row = l32 + 32 * mt;
                 kf[mt][ks] = *(const bf16x8*)(k_lds + row * 128 + swz(row, 2 * ks + half) * 16);
             }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (c < n) gather_tile(k_rsrc, origin_next, voff, k_lds);
+    };
 
-        // ---- S^T = K Q^T
+    // K(0) has landed (loads complete in order; K(0) is older than the 16 loads
+    // of V(0) and Q); once its fragments are out, K(1) may overwrite the tile
+    bf16x8 kf[2][4];
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    read_k_frags(kf);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    gather_tile(n >= 1 ? k_rsrc : null_rsrc, origin_of(block_at(n >= 1 ? 1 : 0)), voff, k_lds);
+
+    for (int c = 0; c <= n; ++c) {
+        // ---- S^T = K(c) Q^T
         f32x16 sacc[2][2];   // [mt][nt]
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
@@ -240,26 +279,22 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
                         kf[mt][ks], qf[nt][ks], sacc[mt][nt], 0, 0, 0);
             }
 
-        // ---- running maximum; rescale only when it has moved far
-        float cand[2];
-        bool grow = false;
+        // ---- P^T = exp2(S^T c2 - m_ref) against the current reference, one
+        // query half at a time; the slow path finds a new reference from the
+        // row maxima, rescales O and the normaliser and recomputes the weights
+        bf16x8 pf[2][4];     // [nt][kk]: keys 16 kk .. 16 kk + 15
+        bf16x8 vf[2][4];     // [dt][kk]
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            float mx = max3(sacc[0][nt][0], sacc[0][nt][1], sacc[0][nt][2]);
+            float rs = softmax_weights(sacc, nt, c2, -m_ref[nt], pf);
+            if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) {
+                float mx = sacc[0][nt][0];
 #pragma unroll
-            for (int r = 3; r < 15; r += 2) mx = max3(mx, sacc[0][nt][r], sacc[0][nt][r + 1]);
-            mx = max3(mx, sacc[0][nt][15], sacc[1][nt][0]);
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[0][nt][r]);
 #pragma unroll
-            for (int r = 1; r < 15; r += 2) mx = max3(mx, sacc[1][nt][r], sacc[1][nt][r + 1]);
-            mx = fmaxf(mx, sacc[1][nt][15]);
-            mx = fmaxf(mx, swap32(mx));
-            cand[nt] = mx * c2;
-            grow |= cand[nt] > m_ref[nt] + kRescaleGap;
-        }
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-                const float m_new = fmaxf(m_ref[nt], cand[nt]);
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[1][nt][r]);
+                mx = fmaxf(mx, swap32(mx));
+                const float m_new = fmaxf(m_ref[nt], mx * c2);
                 const float alpha = __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
                 m_ref[nt] = m_new;
                 l_run[nt] *= alpha;
@@ -267,58 +302,46 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
                 for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+                rs = softmax_weights(sacc, nt, c2, -m_new, pf);
             }
-        }
+            l_run[nt] += rs;
 
-        // ---- P^T = exp2(S^T c2 - m_ref), packed to bf16 as B operands; the row
-        // sums are taken over the rounded weights, two per instruction
-        bf16x8 pf[2][4];     // [nt][kk]: keys 16 kk .. 16 kk + 15
+            if (nt == 0) {
+                // V(c) has landed (it is older than the 8 loads of the K(c+1)
+                // gather): request its fragments now that half of S is dead;
+                // they arrive while the other half's weights are computed
+                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const float neg_m = -m_ref[nt];
-            float rs = l_run[nt];
+                for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+                    for (int kk = 0; kk < 4; ++kk) {
+                        bf16x4 part[2];
 #pragma unroll
-                for (int h8 = 0; h8 < 2; ++h8) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int e = 0; e < 8; e += 2) {
-                        const float p0 = __builtin_amdgcn_exp2f(
-                            fmaf(sacc[mt][nt][8 * h8 + e], c2, neg_m));
-                        const float p1 = __builtin_amdgcn_exp2f(
-                            fmaf(sacc[mt][nt][8 * h8 + e + 1], c2, neg_m));
-                        w[e >> 1] = pack_bf16(p0, p1);
-                        rs = __builtin_amdgcn_fdot2_f32_bf16(
-                            __builtin_bit_cast(bf16x2, w[e >> 1]), ones, rs, false);
+                        for (int rd = 0; rd < 2; ++rd) {
+                            const int row = 16 * kk + 8 * rd + v_row_in_step;
+                            const int col = v_col + 32 * dt;   // channel, multiple of 4
+                            const unsigned char* p =
+                                v_lds + row * 128 + swz(row, col >> 3) * 16 + (col & 7) * 2;
+                            part[rd] =
+                                __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p));
+                        }
+                        vf[dt][kk] =
+                            __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
                     }
-                    const uint4 packed = make_uint4(w[0], w[1], w[2], w[3]);
-                    pf[nt][2 * mt + h8] = __builtin_bit_cast(bf16x8, packed);
-                }
-            l_run[nt] = rs;
+            }
         }
 
-        // ---- V(c) has landed: V^T fragments through the transposing read
-        if (c < n) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        bf16x8 vf[2][4];     // [dt][kk]
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                bf16x4 part[2];
-#pragma unroll
-                for (int rd = 0; rd < 2; ++rd) {
-                    const int row = 16 * kk + 8 * rd + v_row_in_step;
-                    const int col = v_col + 32 * dt;           // channel, multiple of 4
-                    const unsigned char* p =
-                        v_lds + row * 128 + swz(row, col >> 3) * 16 + (col & 7) * 2;
-                    part[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p));
-                }
-                vf[dt][kk] = __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
-            }
+        // ---- V fragments are in registers: the V tile may take V(c+1)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (c < n) gather_tile(v_rsrc, origin_next, voff, v_lds);
+        gather_tile(c + 1 <= n ? v_rsrc : null_rsrc, origin_of(block_at(c + 1 <= n ? c + 1 : n)),
+                    voff, v_lds);
+
+        // ---- K(c+1) has landed (older than the 8 loads just issued): request
+        // its fragments; they arrive during the PV product
+        if (c < n) {
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            read_k_frags(kf);
+        }
 
         // ---- O^T += V^T P^T
 #pragma unroll
@@ -329,6 +352,13 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
                 for (int kk = 0; kk < 4; ++kk)
                     oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         vf[dt][kk], pf[nt][kk], oacc[dt][nt], 0, 0, 0);
+
+        // ---- K fragments are in registers: the K tile may take K(c+2)
+        if (c < n) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            gather_tile(c + 2 <= n ? k_rsrc : null_rsrc,
+                        origin_of(block_at(c + 2 <= n ? c + 2 : n)), voff, k_lds);
+        }
     }
 
     // ---- epilogue: normalise, store O rows (4 consecutive channels per store)
