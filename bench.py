@@ -30,9 +30,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per forward launch measured with rocprofv3 --pmc (FETCH_SIZE, then
-# WRITE_SIZE, each scaled by the same counter on a plain copy kernel); see the
-# summaries under profiles/.  None until measured for a workload.
-MEASURED_FWD_TRAFFIC_BYTES = {}
+# WRITE_SIZE, each scaled by the same counter on a plain copy kernel of known
+# size: 2048 and 1024 bytes per count); profiles/fwd_mfma_b64_d64_config3.md.
+# None for workloads that have not been measured.
+MEASURED_FWD_TRAFFIC_BYTES = {3: 17.84e9 + 1.69e9}
 
 
 def parse_args():
