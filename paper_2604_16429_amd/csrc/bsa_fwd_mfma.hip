@@ -27,14 +27,17 @@
 //     chunk), because that load always writes lanes to consecutive LDS
 //     addresses.
 // Order of work for pair c (K(c) fragments are already in registers):
-//   S^T = K(c) Q^T (16 MFMAs); V(c) fragments are requested from LDS while the
-//   weights P(c) are computed on the vector ALU; once they are in registers the
-//   V(c+1) gather may overwrite the V tile; the K(c+1) fragments are requested
-//   before O^T += V(c)^T P(c)^T (16 MFMAs) so that the next pair starts without
-//   waiting for LDS; then the K(c+2) gather overwrites the K tile.  The matrix
-//   work of a pair thus forms one run (PV of pair c, QK of pair c+1) and the
-//   vector work another; two wavefronts per SIMD overlap one wave's run of
-//   MFMAs with the other's exponentials.
+//   1. S^T = K(c) Q^T, 16 MFMAs, with the 8 loads of the K(c+1) gather issued
+//      between them (the K tile in LDS is free: its fragments are in registers);
+//   2. the weights P(c) on the vector ALU; half-way, the V(c) fragments are
+//      requested from LDS;
+//   3. the K(c+1) fragments are requested from LDS;
+//   4. O^T += V(c)^T P(c)^T, 16 MFMAs, with the 8 loads of the V(c+1) gather
+//      issued between them.
+// A gather issued in one burst would hold the wavefront at the CU's shared
+// address unit for hundreds of cycles; spread over a run of MFMAs, whose issue
+// is paced by the matrix pipe anyway, it costs nothing.  Two wavefronts per
+// SIMD overlap one wave's MFMA runs with the other's exponentials.
 //
 // Softmax without a row maximum per pair.  m_ref is the reference the
 // exponentials are taken against.  A pair first computes its weights against
@@ -168,25 +171,19 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const __amdgpu_buffer_rsrc_t null_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, 0, 0x00020000);
 
-    // Attended blocks (own block + selection) in ascending block order when
-    // they fit one wavefront: query blocks that run at the same time on an XCD
-    // then sweep the slice's K/V in the same direction and find each other's
-    // tiles in L2.  The result does not depend on the order (up to rounding).
+    // Visiting order: the own block first (it needs nothing from sel_idx, so
+    // its gathers start at once), then the selected blocks in ascending block
+    // order when they fit one wavefront: query blocks that run at the same time
+    // on an XCD then sweep the slice's K/V in the same direction and find each
+    // other's tiles in L2.  The result does not depend on the order (up to
+    // rounding).  The order is computed after the first gathers are in flight;
     // order_v: lane c holds the c-th block to visit.
     const bool sorted = n + 1 <= 64;
-    int order_v = 0;
-    if (sorted) {
-        const int mine = lane == 0 ? i : (lane <= n ? sel_row[lane - 1] : 0x7fffffff);
-        int rank = 0;
-        for (int t = 0; t <= n; ++t)
-            rank += __builtin_amdgcn_readlane(mine, t) < mine ? 1 : 0;
-        if (lane <= n) order_s[rank] = mine;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        order_v = order_s[lane];
-    }
+    int order_v = i;
     auto block_at = [&](int c) -> int {
+        if (c == 0) return i;
         if (sorted) return __builtin_amdgcn_readlane(order_v, c);
-        return c == 0 ? i : sel_row[c - 1];
+        return sel_row[c - 1];
     };
 
     // byte offset (inside a block) of the 16-byte chunk this lane gathers in
@@ -228,6 +225,17 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         }
     }
 
+    if (sorted) {
+        // lane l in 1..n holds a selected block; rank = 1 + number of smaller ones
+        const int mine = (lane >= 1 && lane <= n) ? sel_row[lane - 1] : 0x7fffffff;
+        int rank = 1;
+        for (int t = 1; t <= n; ++t)
+            rank += __builtin_amdgcn_readlane(mine, t) < mine ? 1 : 0;
+        if (lane >= 1 && lane <= n) order_s[rank] = mine;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        order_v = order_s[lane];
+    }
+
     const float c2 = g.scale * 1.4426950408889634f;
     const f32x16 zero16 = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
                            0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
@@ -256,30 +264,36 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
             }
     };
 
-    // K(0) has landed (loads complete in order; K(0) is older than the 16 loads
-    // of V(0) and Q); once its fragments are out, K(1) may overwrite the tile
+    // K(0) has landed: loads complete in order, and K(0) is older than the loads
+    // of V(0) and Q and of the selection row (8 + 8 + 1)
     bf16x8 kf[2][4];
-    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(17)" ::: "memory");
     read_k_frags(kf);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    gather_tile(n >= 1 ? k_rsrc : null_rsrc, origin_of(block_at(n >= 1 ? 1 : 0)), voff, k_lds);
 
     for (int c = 0; c <= n; ++c) {
-        // ---- S^T = K(c) Q^T
+        const uint32_t origin_next = origin_of(block_at(c < n ? c + 1 : n));
+        const __amdgpu_buffer_rsrc_t k_next = c < n ? k_rsrc : null_rsrc;
+        const __amdgpu_buffer_rsrc_t v_next = c < n ? v_rsrc : null_rsrc;
+
+        // ---- 1. S^T = K(c) Q^T, with the K(c+1) gather between the MFMAs (the
+        // K fragments are in registers, so the K tile may be overwritten)
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         f32x16 sacc[2][2];   // [mt][nt]
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                sacc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][0], qf[nt][0],
-                                                                       zero16, 0, 0, 0);
+            for (int nt = 0; nt < 2; ++nt) {
 #pragma unroll
-                for (int ks = 1; ks < 4; ++ks)
+                for (int mt = 0; mt < 2; ++mt)
                     sacc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        kf[mt][ks], qf[nt][ks], sacc[mt][nt], 0, 0, 0);
+                        kf[mt][ks], qf[nt][ks], ks == 0 ? zero16 : sacc[mt][nt], 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    k_next, LDS_PTR(void, k_lds + (2 * ks + nt) * 1024), 16, voff[2 * ks + nt],
+                    origin_next, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
 
-        // ---- P^T = exp2(S^T c2 - m_ref) against the current reference, one
+        // ---- 2. P^T = exp2(S^T c2 - m_ref) against the current reference, one
         // query half at a time; the slow path finds a new reference from the
         // row maxima, rescales O and the normaliser and recomputes the weights
         bf16x8 pf[2][4];     // [nt][kk]: keys 16 kk .. 16 kk + 15
@@ -331,34 +345,26 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
             }
         }
 
-        // ---- V fragments are in registers: the V tile may take V(c+1)
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        gather_tile(c + 1 <= n ? v_rsrc : null_rsrc, origin_of(block_at(c + 1 <= n ? c + 1 : n)),
-                    voff, v_lds);
+        // ---- 3. K(c+1) has landed (nothing younger is in flight): request its
+        // fragments; they arrive during the PV product
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        if (c < n) read_k_frags(kf);
 
-        // ---- K(c+1) has landed (older than the 8 loads just issued): request
-        // its fragments; they arrive during the PV product
-        if (c < n) {
-            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-            read_k_frags(kf);
-        }
-
-        // ---- O^T += V^T P^T
+        // ---- 4. O^T += V^T P^T, with the V(c+1) gather between the MFMAs (the
+        // V fragments are in registers, so the V tile may be overwritten)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
+            for (int nt = 0; nt < 2; ++nt) {
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
+                for (int dt = 0; dt < 2; ++dt)
                     oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         vf[dt][kk], pf[nt][kk], oacc[dt][nt], 0, 0, 0);
-
-        // ---- K fragments are in registers: the K tile may take K(c+2)
-        if (c < n) {
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            gather_tile(c + 2 <= n ? k_rsrc : null_rsrc,
-                        origin_of(block_at(c + 2 <= n ? c + 2 : n)), voff, k_lds);
-        }
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    v_next, LDS_PTR(void, v_lds + (2 * kk + nt) * 1024), 16, voff[2 * kk + nt],
+                    origin_next, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
     }
 
     // ---- epilogue: normalise, store O rows (4 consecutive channels per store)
