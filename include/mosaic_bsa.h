@@ -127,7 +127,9 @@ int mosaic_bsa_fwd(const mosaic_bsa_params *params, const void *q, const void *k
  *   sel_idx             in   device, same contract as in mosaic_bsa_fwd
  *   dq, dk, dv          out  device, [B, heads, N, D], element type of q
  *   workspace                device scratch of
- *                            mosaic_bsa_workspace_bytes(.., OP_BWD) bytes.
+ *                            mosaic_bsa_workspace_bytes(.., OP_BWD) bytes; on
+ *                            return it holds delta_l = dout_l . out_l, fp32
+ *                            [B, heads, N].
  * dk/dv of a key block are reduced over the query blocks that attend to it in
  * a fixed order (no floating-point atomics): results are run-to-run identical.
  */

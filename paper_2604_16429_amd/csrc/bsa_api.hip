@@ -62,6 +62,11 @@ size_t select_workspace(const Checked& c)
     return 2 * align_up((size_t)c.BH * c.g.n_blocks * c.D * sizeof(float));
 }
 
+size_t bwd_workspace(const Checked& c)
+{
+    return align_up((size_t)c.BH * (size_t)c.g.n_tokens * sizeof(float));   // delta
+}
+
 }  // namespace
 
 extern "C" size_t mosaic_bsa_workspace_bytes(const mosaic_bsa_params* params, int op)
@@ -71,7 +76,7 @@ extern "C" size_t mosaic_bsa_workspace_bytes(const mosaic_bsa_params* params, in
     switch (op) {
     case MOSAIC_BSA_OP_SELECT: return select_workspace(c);
     case MOSAIC_BSA_OP_FWD: return 0;
-    case MOSAIC_BSA_OP_BWD: return 0;
+    case MOSAIC_BSA_OP_BWD: return bwd_workspace(c);
     }
     return 0;
 }
@@ -126,14 +131,19 @@ extern "C" int mosaic_bsa_bwd(const mosaic_bsa_params* params, const void* q, co
                               const int32_t* sel_idx, void* dq, void* dk, void* dv,
                               void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
-    (void)hip_stream;
     Checked c;
     if (int rc = check_params(params, &c)) return rc;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return MOSAIC_BSA_ERR_NULL;
     if (c.g.n_select > 0 && !sel_idx) return MOSAIC_BSA_ERR_NULL;
-    return MOSAIC_BSA_ERR_OP;   // backward kernels not built yet
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dout) ||
+        misaligned(dq) || misaligned(dk) || misaligned(dv) || misaligned(workspace))
+        return MOSAIC_BSA_ERR_ALIGN;
+    if (!workspace || workspace_bytes < bwd_workspace(c)) return MOSAIC_BSA_ERR_WORKSPACE;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const hipError_t e = bsa::launch_bwd(c.is_bf16, q, k, v, out, lse, dout, sel_idx, dq, dk, dv,
+                                         (float*)workspace, c.g, c.D, c.BH, stream);
+    return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
 }
 
 extern "C" const char* mosaic_bsa_strerror(int code)

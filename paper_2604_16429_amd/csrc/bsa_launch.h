@@ -29,4 +29,10 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const in
                            void* out, float* lse, const Geom& g, int D, int64_t BH,
                            hipStream_t stream);
 
+// Backward with the selection fixed; `delta` is fp32 scratch of B*heads*N floats.
+hipError_t launch_bwd(bool is_bf16, const void* q, const void* k, const void* v, const void* out,
+                      const float* lse, const void* dout, const int32_t* sel_idx, void* dq,
+                      void* dk, void* dv, float* delta, const Geom& g, int D, int64_t BH,
+                      hipStream_t stream);
+
 }  // namespace bsa

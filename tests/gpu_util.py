@@ -55,3 +55,17 @@ def gpu_fwd(cfg, q, k, v, idx, n_select=None, softmax_scale=0.0):
                        n_select, softmax_scale)
     torch.cuda.synchronize()
     return out.float().cpu().numpy(), lse.cpu().numpy()
+
+
+def gpu_bwd(cfg, q, k, v, dout, idx, n_select=None, softmax_scale=0.0):
+    """Forward then backward on the GPU; returns (dq, dk, dv) as fp32 numpy."""
+    p = params_of(cfg, n_select, softmax_scale)
+    idx_d = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).to("cuda")
+    q_d, k_d, v_d, do_d = (to_dev(x, cfg) for x in (q, k, v, dout))
+    out, lse = fwd_dev(cfg, q_d, k_d, v_d, idx_d, n_select, softmax_scale)
+    dq, dk, dv = (torch.full_like(q_d, float("nan")) for _ in range(3))
+    ws = torch.empty(max(M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD), 256),
+                     dtype=torch.uint8, device="cuda")
+    M.mosaic_bsa_bwd(p, q_d, k_d, v_d, out, lse, do_d, idx_d, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    return tuple(t.float().cpu().numpy() for t in (dq, dk, dv))

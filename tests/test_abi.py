@@ -44,6 +44,7 @@ def test_workspace_bytes():
     per = (1 * 2 * m * 32 * 4 + 255) // 256 * 256
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_SELECT) == 2 * per
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_FWD) == 0
+    assert M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD) == 1 * 2 * 2048 * 4
     assert M.mosaic_bsa_workspace_bytes(good(head_dim=48), binding.OP_SELECT) == 0
 
 
@@ -91,6 +92,16 @@ def test_null_alignment_and_workspace_errors():
     assert e.value.code == -1
     with pytest.raises(M.BsaError) as e:
         M.mosaic_bsa_fwd(p, fake, fake, fake + 8, fake, fake, None, None, stream=0)
+    assert e.value.code == -7
+    wb = M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD)
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_bwd(p, *([fake] * 5), None, *([fake] * 4), fake, stream=0, workspace_bytes=wb)
+    assert e.value.code == -1
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_bwd(p, *([fake] * 10), fake, stream=0, workspace_bytes=wb - 1)
+    assert e.value.code == -6
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_bwd(p, *([fake] * 9), fake + 2, fake, stream=0, workspace_bytes=wb)
     assert e.value.code == -7
 
 

@@ -159,3 +159,54 @@ def test_arbitrary_selection_and_explicit_scale(G, oracle):
     out_ref, lse_ref = oracle.fwd(s, q, k, v, idx, scale=0.2)
     out, lse = G.gpu_fwd(cfg, q, k, v, idx, softmax_scale=0.2)
     check_out(cfg, out, lse, out_ref, lse_ref)
+
+
+# --------------------------------------------------------------------------
+# backward (selection held fixed)
+# --------------------------------------------------------------------------
+def check_grads(cfg, got, ref):
+    """fp32 mode: 1e-4 of the largest gradient entry.  bf16 mode: 2e-2 of
+    max(1, largest entry) -- inputs, O and the stored gradients are bf16."""
+    for name, g, r in zip(("dq", "dk", "dv"), got, ref):
+        scale = max(1.0, np.abs(r).max()) if cfg.dtype == "bf16" else np.abs(r).max()
+        tol = (2e-2 if cfg.dtype == "bf16" else 1e-4) * scale
+        err = np.abs(g - r).max()
+        assert err <= tol, f"{name}: max error {err} > {tol}"
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("H,W,bh,bw,D,n", [
+    (32, 64, 8, 8, 32, 4),      # the tiny-grid configuration
+    (48, 96, 8, 16, 128, 12),   # tile and head dim of the gradient configuration
+    (12, 18, 6, 6, 32, 3),      # b = 36: ragged against the 64-row chunk
+    (16, 48, 8, 12, 64, 5),     # b = 96
+    (8, 8, 8, 8, 64, 0),        # single block
+    (16, 16, 4, 4, 64, 15),     # every block selected: dense gradient
+])
+def test_backward_matches_oracle(G, oracle, dtype, H, W, bh, bw, D, n):
+    cfg = shape_ns(1, 2, H, W, bh, bw, D, n, dtype)
+    q, k, v = rand_qkv(cfg, 300 + H + D)
+    dout = rand_qkv(cfg, 301 + H + D)[0]
+    if dtype == "bf16":
+        q, k, v, dout = (round_to_bf16(x) for x in (q, k, v, dout))
+    s = oracle.shape_of(cfg)
+    idx = oracle.select(s, q, k)
+    ref = oracle.bwd(s, q, k, v, dout, idx)
+    got = G.gpu_bwd(cfg, q, k, v, dout, idx)
+    check_grads(cfg, got, ref)
+
+
+def test_backward_gradient_configuration_fields(G, oracle):
+    """Seeded smooth fields of the gradient configuration (tile 8x16, D = 128,
+    n = 12, dO white) on a reduced grid, arbitrary selection order; reruns are
+    bitwise identical (fixed-order reduction, no float atomics)."""
+    p = make_problem(5, batch=1, heads=2, grid_h=48, grid_w=96)
+    cfg = p.cfg
+    s = oracle.shape_of(cfg)
+    idx = random_selection(cfg, 31)
+    ref = oracle.bwd(s, p.q, p.k, p.v, p.dout, idx)
+    got = G.gpu_bwd(cfg, p.q, p.k, p.v, p.dout, idx)
+    check_grads(cfg, got, ref)
+    again = G.gpu_bwd(cfg, p.q, p.k, p.v, p.dout, idx)
+    for a, b in zip(got, again):
+        assert np.array_equal(a, b)
