@@ -1,5 +1,7 @@
 // Block-sparse attention forward on the gfx950 matrix cores (bf16 MFMA, fp32
-// online softmax).  Specialised for head dim 64 and tiles of 64 tokens.
+// online softmax).  Specialised for head dim 64 and tiles of 64*T tokens whose
+// width divides 64; a tile is processed as T sub-blocks of 64 queries (one
+// wavefront each) against T sub-tiles of 64 keys per attended block.
 //
 // Every token of query block i attends, in one softmax, to the tokens of block
 // i and of its n selected blocks (fine-grained attention equation plus the
@@ -130,7 +132,7 @@ constexpr float kSumLimit = 4096.0f;
 __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
-    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd)
+    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd, int subs)
 {
     constexpr int D = 64;
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds[64 * 128];
@@ -146,19 +148,27 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     // to XCDs whole (slice s runs on XCD s % 8, its query blocks back to back),
     // so the K/V tiles a slice's query blocks share are fetched into one L2
     // instead of eight.  The last BH % 8 slices use the plain linear order.
-    int i;
+    // A work item is one sub-block of 64 queries: item = block * subs + sub.
+    int i, qsub;
     int64_t bh_idx;
     {
         const int64_t w = blockIdx.x;
-        if (w < slices_xcd * g.n_blocks) {
+        const int64_t per_slice = (int64_t)g.n_blocks * subs;
+        int64_t item;
+        if (w < slices_xcd * per_slice) {
             const int64_t seq = w >> 3;
-            bh_idx = (seq / g.n_blocks) * 8 + (w & 7);
-            i = (int)(seq % g.n_blocks);
+            bh_idx = (seq / per_slice) * 8 + (w & 7);
+            item = seq % per_slice;
         } else {
-            bh_idx = w / g.n_blocks;
-            i = (int)(w % g.n_blocks);
+            bh_idx = w / per_slice;
+            item = w % per_slice;
         }
+        i = (int)(item / subs);
+        qsub = (int)(item - (int64_t)i * subs);
     }
+    // byte distance between consecutive 64-token sub-tiles of a block: 64/bw
+    // grid rows (the tile width divides 64)
+    const uint32_t sub_stride = (uint32_t)((64 / g.block_w) * g.grid_w * (D * 2));
     const int64_t base = bh_idx * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     q += base; out += base;
@@ -216,7 +226,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         const int64_t tok0 = (int64_t)br * g.block_h * g.grid_w + (int64_t)bc * g.block_w;
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            const int t = l32 + 32 * nt;
+            const int t = 64 * qsub + l32 + 32 * nt;
             const int rr = t / g.block_w, cc = t - rr * g.block_w;
             q_tok[nt] = tok0 + (int64_t)rr * g.grid_w + cc;
 #pragma unroll
@@ -270,10 +280,16 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     asm volatile("s_waitcnt vmcnt(17)" ::: "memory");
     read_k_frags(kf);
 
-    for (int c = 0; c <= n; ++c) {
-        const uint32_t origin_next = origin_of(block_at(c < n ? c + 1 : n));
-        const __amdgpu_buffer_rsrc_t k_next = c < n ? k_rsrc : null_rsrc;
-        const __amdgpu_buffer_rsrc_t v_next = c < n ? v_rsrc : null_rsrc;
+    // pairs: attended block cb = 0..n (visiting order), key sub-tile ct = 0..subs-1
+    int cb = 0, ct = 0;
+    const int pairs = (n + 1) * subs;
+    for (int c = 0; c < pairs; ++c) {
+        const bool has_next = c + 1 < pairs;
+        if (++ct == subs) { ct = 0; ++cb; }           // (cb, ct) now names pair c+1
+        const uint32_t origin_next =
+            origin_of(block_at(has_next ? cb : n)) + (has_next ? ct : 0) * sub_stride;
+        const __amdgpu_buffer_rsrc_t k_next = has_next ? k_rsrc : null_rsrc;
+        const __amdgpu_buffer_rsrc_t v_next = has_next ? v_rsrc : null_rsrc;
 
         // ---- 1. S^T = K(c) Q^T, with the K(c+1) gather between the MFMAs (the
         // K fragments are in registers, so the K tile may be overwritten)
@@ -348,7 +364,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         // ---- 3. K(c+1) has landed (nothing younger is in flight): request its
         // fragments; they arrive during the PV product
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        if (c < n) read_k_frags(kf);
+        if (has_next) read_k_frags(kf);
 
         // ---- 4. O^T += V^T P^T, with the V(c+1) gather between the MFMAs (the
         // V fragments are in registers, so the V tile may be overwritten)
@@ -392,9 +408,12 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
 
 bool fwd_mfma_supported(bool is_bf16, const Geom& g, int D)
 {
-    // 16-byte chunks of a token row must not straddle tokens: always true for
-    // D = 64 bf16 (128 bytes per token).
-    return is_bf16 && D == 64 && g.block_tokens == 64;
+    // tiles of 64*T tokens whose width divides 64: every 64-token sub-tile is
+    // then a whole number of tile rows, a fixed byte distance apart
+    // (a token row is 128 bytes, so 16-byte chunks never straddle tokens);
+    // buffer offsets inside a slice are 32-bit
+    return is_bf16 && D == 64 && g.block_tokens % 64 == 0 && 64 % g.block_w == 0 &&
+           g.n_tokens * D * 2 < ((int64_t)1 << 31);
 }
 
 hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const int32_t* sel_idx,
@@ -402,10 +421,11 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const in
                            hipStream_t stream)
 {
     (void)D;
-    dim3 grid((unsigned)(BH * g.n_blocks));
+    const int subs = g.block_tokens / 64;
+    dim3 grid((unsigned)(BH * g.n_blocks * subs));
     hipLaunchKernelGGL(fwd_mfma_b64_d64_kernel, grid, dim3(64), 0, stream, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
-                       BH - BH % 8);
+                       BH - BH % 8, subs);
     return hipGetLastError();
 }
 

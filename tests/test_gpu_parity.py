@@ -83,6 +83,26 @@ def test_edge_shapes(G, oracle, dtype, H, W, bh, bw, D, n):
     full_parity(G, oracle, cfg, q, k, v)
 
 
+@pytest.mark.parametrize("H,W,bh,bw,n", [
+    (64, 96, 16, 16, 5),     # 256-token tiles (the 0.25 degree configuration's tile)
+    (32, 64, 4, 32, 3),      # 128-token tiles, wide
+    (32, 64, 16, 4, 6),      # 64-token tiles, narrow
+    (48, 64, 24, 8, 2),      # 192-token tiles: three sub-blocks
+])
+def test_mfma_tile_shapes(G, oracle, H, W, bh, bw, n):
+    """bf16, D = 64 tiles of 64*T tokens (matrix-core forward kernel)."""
+    cfg = shape_ns(2, 2, H, W, bh, bw, 64, n, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 500 + bh + bw))
+    full_parity(G, oracle, cfg, q, k, v)
+
+
+def test_config4_quarter_degree_reduced(G, oracle):
+    """The 0.25 degree configuration's tiles, head dim and n on a reduced grid
+    (full forward against the oracle), seeded smooth fields."""
+    p = make_problem(4, heads=2, grid_h=144, grid_w=288)
+    full_parity(G, oracle, p.cfg, p.q, p.k, p.v)
+
+
 def test_ties_and_exact_arithmetic_selection(G, oracle):
     """Constant keys (all scores tie) and quantised data (exact arithmetic):
     the tie-break and the never-select-yourself rule must match bit for bit."""
