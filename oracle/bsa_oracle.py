@@ -161,37 +161,37 @@ def fwd_blocks(s, q, k, v, sel_idx, pairs, scale: float = 0.0):
     """Forward for the listed (batch*head, block) pairs only.
 
     Returns (out [cnt, b, D], lse [cnt, b]) float64 with rows in in-tile order.
+    Works slice by slice on views of the inputs (no copies of the tensors).
     """
     B, h, N, D, b, m = _dims(s)
-    q, pq = _f32(q)
-    k, pk = _f32(k)
-    v, pv = _f32(v)
+    q, _ = _f32(q)
+    k, _ = _f32(k)
+    v, _ = _f32(v)
     _check(s, q, k, v)
-    sel_idx, pi = _i32(sel_idx)
+    sel_idx, _ = _i32(sel_idx)
     pairs = np.ascontiguousarray(pairs, dtype=np.int64).reshape(-1, 2)
-    # the C routine writes rows in place of a full-size output; keep only the
-    # batch*head slices that are touched
-    gs = np.unique(pairs[:, 0])
-    remap = {int(g): r for r, g in enumerate(gs)}
-    sub = _shape(1, len(gs), s.grid_h, s.grid_w, s.block_h, s.block_w, D,
-                 s.n_select)
-    q_s = np.ascontiguousarray(q.reshape(B * h, N, D)[gs])
-    k_s = np.ascontiguousarray(k.reshape(B * h, N, D)[gs])
-    v_s = np.ascontiguousarray(v.reshape(B * h, N, D)[gs])
-    i_s = np.ascontiguousarray(sel_idx.reshape(B * h, m, s.n_select)[gs])
-    p_s = np.array([[remap[int(g)], i] for g, i in pairs], dtype=np.int64)
-    out = np.zeros((len(gs), N, D), dtype=np.float64)
-    lse = np.zeros((len(gs), N), dtype=np.float64)
-    _load().oracle_fwd_blocks(
-        ctypes.byref(sub), q_s.ctypes.data_as(ctypes.c_void_p),
-        k_s.ctypes.data_as(ctypes.c_void_p), v_s.ctypes.data_as(ctypes.c_void_p),
-        i_s.ctypes.data_as(ctypes.c_void_p), ctypes.c_double(scale),
-        p_s.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(len(p_s)),
-        out.ctypes.data_as(ctypes.c_void_p), lse.ctypes.data_as(ctypes.c_void_p))
-    rows = np.array([[token_of(s, int(i), t) for t in range(b)]
-                     for _, i in pairs], dtype=np.int64)
-    gsel = p_s[:, 0][:, None]
-    return out[gsel, rows], lse[gsel, rows]
+    q3, k3, v3 = (x.reshape(B * h, N, D) for x in (q, k, v))
+    i3 = sel_idx.reshape(B * h, m, s.n_select)
+    sub = _shape(1, 1, s.grid_h, s.grid_w, s.block_h, s.block_w, D, s.n_select)
+    out = np.empty((len(pairs), b, D), dtype=np.float64)
+    lse = np.empty((len(pairs), b), dtype=np.float64)
+    full_o = np.zeros((N, D), dtype=np.float64)
+    full_l = np.zeros((N,), dtype=np.float64)
+    for g in np.unique(pairs[:, 0]):
+        where = np.nonzero(pairs[:, 0] == g)[0]
+        blocks = pairs[where, 1]
+        p_s = np.ascontiguousarray(np.stack([np.zeros_like(blocks), blocks], axis=1))
+        _load().oracle_fwd_blocks(
+            ctypes.byref(sub), q3[g].ctypes.data_as(ctypes.c_void_p),
+            k3[g].ctypes.data_as(ctypes.c_void_p), v3[g].ctypes.data_as(ctypes.c_void_p),
+            i3[g].ctypes.data_as(ctypes.c_void_p), ctypes.c_double(scale),
+            p_s.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(len(p_s)),
+            full_o.ctypes.data_as(ctypes.c_void_p), full_l.ctypes.data_as(ctypes.c_void_p))
+        for w, i in zip(where, blocks):
+            rows = np.array([token_of(s, int(i), t) for t in range(b)], dtype=np.int64)
+            out[w] = full_o[rows]
+            lse[w] = full_l[rows]
+    return out, lse
 
 
 def block_weights(s, q, k, v, sel_idx, g: int, i: int, scale: float = 0.0):

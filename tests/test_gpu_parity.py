@@ -182,6 +182,64 @@ def test_arbitrary_selection_and_explicit_scale(G, oracle):
 
 
 # --------------------------------------------------------------------------
+# full sizes, in the launch configuration the benchmark times
+# --------------------------------------------------------------------------
+def full_size_check(G, oracle, p, pairs):
+    """Selection compared in full (bit-exact); forward compared on sampled query
+    blocks that the oracle computes one by one."""
+    cfg = p.cfg
+    s = oracle.shape_of(cfg)
+    q_d, k_d, v_d = (G.to_dev(x, cfg) for x in (p.q, p.k, p.v))
+    idx_d = G.select_dev(cfg, q_d, k_d)
+    out_d, lse_d = G.fwd_dev(cfg, q_d, k_d, v_d, idx_d)
+    torch.cuda.synchronize()
+    idx = idx_d.cpu().numpy()
+    assert np.array_equal(idx, oracle.select(s, p.q, p.k))
+    out_ref, lse_ref = oracle.fwd_blocks(s, p.q, p.k, p.v, idx, pairs)
+    bh = cfg.batch * cfg.heads
+    out_t = out_d.view(bh, cfg.n_tokens, cfg.head_dim)
+    lse_t = lse_d.view(bh, cfg.n_tokens)
+    for w, (g, i) in enumerate(pairs):
+        rows = torch.tensor([oracle.token_of(s, int(i), t) for t in range(cfg.block_tokens)],
+                            device="cuda")
+        o = out_t[int(g)][rows].float().cpu().numpy()
+        l = lse_t[int(g)][rows].cpu().numpy()
+        assert np.isfinite(o).all()
+        assert np.abs(o - out_ref[w]).max() <= 2e-2, (g, i)
+        assert np.abs(l - lse_ref[w]).max() <= 3e-3, (g, i)
+    # every output row was written (the buffers were pre-filled with NaN)
+    assert bool(torch.isfinite(out_d.float()).all()) and bool(torch.isfinite(lse_d).all())
+
+
+def test_config3_full_size_sampled(G, oracle):
+    p = make_problem(3)
+    cfg = p.cfg
+    rng = np.random.default_rng(33)
+    pairs = [[0, i] for i in range(cfg.n_blocks)]                 # member 0, head 0: all blocks
+    for g in rng.choice(cfg.batch * cfg.heads, size=12, replace=False):
+        pairs += [[int(g), int(i)] for i in rng.choice(cfg.n_blocks, size=24, replace=False)]
+    full_size_check(G, oracle, p, np.array(pairs))
+
+
+def test_config4_full_size_sampled(G, oracle):
+    p = make_problem(4)
+    cfg = p.cfg
+    rng = np.random.default_rng(44)
+    pairs = [[int(g), int(i)] for g in range(cfg.batch * cfg.heads)
+             for i in rng.choice(cfg.n_blocks, size=3, replace=False)]
+    full_size_check(G, oracle, p, np.array(pairs))
+
+
+def test_config5_full_size_forward_sampled(G, oracle):
+    p = make_problem(5)
+    cfg = p.cfg
+    rng = np.random.default_rng(55)
+    pairs = [[int(g), int(i)] for g in rng.choice(cfg.batch * cfg.heads, size=8, replace=False)
+             for i in rng.choice(cfg.n_blocks, size=4, replace=False)]
+    full_size_check(G, oracle, p, np.array(pairs))
+
+
+# --------------------------------------------------------------------------
 # backward (selection held fixed)
 # --------------------------------------------------------------------------
 def check_grads(cfg, got, ref):
