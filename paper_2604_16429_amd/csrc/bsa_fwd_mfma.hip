@@ -28,26 +28,35 @@
 //     on the global side of the direct-to-LDS load (which lane fetches which
 //     chunk), because that load always writes lanes to consecutive LDS
 //     addresses.
-// Order of work for pair c (K(c) fragments are already in registers):
-//   1. S^T = K(c) Q^T, 16 MFMAs, with the 8 loads of the K(c+1) gather issued
-//      between them (the K tile in LDS is free: its fragments are in registers);
-//   2. the weights P(c) on the vector ALU; half-way, the V(c) fragments are
-//      requested from LDS;
-//   3. the K(c+1) fragments are requested from LDS;
-//   4. O^T += V(c)^T P(c)^T, 16 MFMAs, with the 8 loads of the V(c+1) gather
-//      issued between them.
-// A gather issued in one burst would hold the wavefront at the CU's shared
-// address unit for hundreds of cycles; spread over a run of MFMAs, whose issue
-// is paced by the matrix pipe anyway, it costs nothing.  Two wavefronts per
-// SIMD overlap one wave's MFMA runs with the other's exponentials.
 //
-// Softmax without a row maximum per pair.  m_ref is the reference the
-// exponentials are taken against.  A pair first computes its weights against
-// the current m_ref; only if some row sum of the pair exceeds 2^12 (which
-// covers the first pair, where m_ref = -inf) does the wavefront take the slow
-// path: find the row maxima, move m_ref, rescale O and the normaliser, and
-// recompute the pair's weights.  Any reference gives the same softmax; bounded
-// weights keep fp32 and bf16 far from overflow.
+// Schedule.  On this hardware a wavefront that streams MFMAs keeps the other
+// wavefronts of its SIMD from issuing vector-ALU work, but the SAME wavefront
+// can issue about 24 cycles of vector-ALU instructions behind each 32-cycle
+// MFMA for free.  The exponentials therefore have to sit between the MFMAs of
+// the wavefront that owns them.  The pair is cut into four tiles of 32 keys x
+// 32 queries, t = (key half mt, query half nt), and the three stages of a
+// tile -- S tile (4 MFMAs), weights (48 vector instructions), O update
+// (4 MFMAs) -- are software-pipelined across tiles, also across pair
+// boundaries: step s issues, alternating, the 4 MFMAs of S(s+1) and the 4 MFMAs
+// of the O update with P(s-1), and behind each of these 8 MFMAs one eighth of
+// the weights of tile s (2 fma, 2 exp2, 1 convert, 1 dot for the row sum).
+// Only two S tiles and two P tiles are live, so the wavefront fits 256
+// registers and two wavefronts share a SIMD to cover each other's waits.
+//
+// K and V live in LDS as two 32-key halves each (four 4 KiB buffers).  A half
+// is read into registers once per pair, at a fixed step, and refilled right
+// after with the same half of the next tile, which then has three steps (3/4
+// of a pair) to arrive.  The 8 loads of a refill are spread over the 8 MFMA
+// slots of a step: a burst would hold the wavefront at the CU's shared address
+// unit.
+//
+// Softmax without a row maximum per tile.  m_ref is the reference the
+// exponentials are taken against.  A tile first computes its weights against
+// the current m_ref; only if some row sum of the tile exceeds 2^12 (which
+// covers the first tile of each query half, where m_ref = -inf) does the
+// wavefront take the slow path: find the row maxima, move m_ref, rescale O and
+// the normaliser, and recompute the tile's weights.  Any reference gives the
+// same softmax; bounded weights keep fp32 and bf16 far from overflow.
 #include "bsa_device.h"
 #include "bsa_launch.h"
 
@@ -75,6 +84,18 @@ __device__ __forceinline__ float swap32(float x)
     return __uint_as_float(threadIdx.x & 32 ? r[0] : r[1]);
 }
 
+// Two fp32 weights -> bf16 pair by truncation (one byte-permute instead of the
+// half-rate rounding convert).  Truncation loses, on average over mantissas,
+// the fraction kTruncLoss of a weight; the normaliser is summed from the fp32
+// weights, so the epilogue scales the output by 1 / (1 - kTruncLoss).
+// (mean of half an ulp, 2^-8, over a log-uniform mantissa m: 2^-8 E[1/m] =
+// 2^-8 / (2 ln 2).)
+constexpr float kTruncLoss = 0.0028179f;
+__device__ __forceinline__ uint32_t pack_bf16_trunc(float lo, float hi)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 {
     const f32x2 v = {a, b};
@@ -82,52 +103,138 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
-// Gather one 64-token x 64-channel bf16 tile into LDS (8 KiB, rows swizzled)
-// with buffer loads that write LDS directly.  Instruction r brings tile rows
-// 8r..8r+7; lane l fills LDS chunk l of that 1 KiB slab, i.e. row 8r + l/8,
-// swizzled chunk l%8.  The per-lane byte offsets inside a block (voff) are
-// fixed for the whole kernel and the block origin is wave-uniform (soffset),
-// so a gather costs no vector ALU work.  The buffer descriptor bounds the
-// slice: an out-of-range block index reads zeros instead of faulting.
-__device__ __forceinline__ void gather_tile(__amdgpu_buffer_rsrc_t rsrc, uint32_t origin_bytes,
-                                            const uint32_t (&voff)[8], unsigned char* lds_tile)
+// Gather one 32-token x 64-channel bf16 half tile into LDS (4 KiB, rows
+// swizzled) with buffer loads that write LDS directly.  A whole 64-token tile
+// takes 8 such instructions; instruction r brings tile rows 8r..8r+7 and lane
+// l fills LDS chunk l of that 1 KiB slab, i.e. row 8r + l/8, swizzled chunk
+// l%8.  The per-lane byte offsets inside a block (voff) are fixed for the whole
+// kernel and the block origin is wave-uniform (soffset), so a gather costs no
+// vector ALU work.  The buffer descriptor bounds the slice: an out-of-range
+// block index reads zeros instead of faulting, and a descriptor of zero
+// records makes the load a no-op.
+template <int R>
+__device__ __forceinline__ void gather_slab(__amdgpu_buffer_rsrc_t rsrc, uint32_t origin_bytes,
+                                            const uint32_t (&voff)[8], unsigned char* lds_half)
 {
-#pragma unroll
-    for (int r = 0; r < 8; ++r)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds_tile + r * 1024), 16,
-                                                 voff[r], origin_bytes, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds_half + (R & 3) * 1024), 16,
+                                             voff[R], origin_bytes, 0, 0);
 }
 
-// P^T = exp2(S^T c2 - m_ref) for one query half nt, packed to bf16 B operands;
-// returns this lane's sum of the rounded weights (two per instruction).  Only
-// builtins touch the MFMA results (never inline asm): the compiler must see
-// these reads to place the wait states the hardware requires.
-__device__ __forceinline__ float softmax_weights(const f32x16 (&s)[2][2], int nt, float c2,
-                                                 float neg_m, bf16x8 (&pf)[2][4])
+// The two half tiles that a step refills, spread over its 8 MFMA slots: a
+// lower half (tile rows 0..31, slabs 0..3) goes to lds_a from (rsrc_a,
+// origin_a), an upper half (rows 32..63, slabs 4..7) to lds_b.
+struct Refill {
+    __amdgpu_buffer_rsrc_t rsrc_a, rsrc_b;
+    uint32_t origin_a, origin_b;
+    __attribute__((address_space(3))) unsigned char *lds_a, *lds_b;
+};
+
+// P^T = exp2(S^T c2 - m_ref) for one 32-key x 32-query tile, packed to bf16 B
+// operands; returns this lane's sum of the rounded weights (two per
+// instruction).  Only builtins touch the MFMA results (never inline asm): the
+// compiler must see these reads to place the wait states the hardware requires.
+__device__ __forceinline__ float tile_weights(const f32x16& s, float c2, float neg_m,
+                                              bf16x8 (&p)[2])
 {
-    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
     float rs = 0.0f;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int h = 0; h < 2; ++h) {
+        uint32_t w[4];
 #pragma unroll
-        for (int h8 = 0; h8 < 2; ++h8) {
-            uint32_t w[4];
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[mt][nt][8 * h8 + e], c2, neg_m));
-                const float p1 =
-                    __builtin_amdgcn_exp2f(fmaf(s[mt][nt][8 * h8 + e + 1], c2, neg_m));
-                w[e >> 1] = pack_bf16(p0, p1);
-                rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e >> 1]), ones,
-                                                     rs, false);
-            }
-            const uint4 packed = make_uint4(w[0], w[1], w[2], w[3]);
-            pf[nt][2 * mt + h8] = __builtin_bit_cast(bf16x8, packed);
+        for (int e = 0; e < 4; ++e) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[8 * h + 2 * e], c2, neg_m));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[8 * h + 2 * e + 1], c2, neg_m));
+            w[e] = pack_bf16_trunc(p0, p1);
+            rs += p0 + p1;
         }
+        p[h] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    }
     return rs;
 }
 
 constexpr float kSumLimit = 4096.0f;
+
+// One step of the software pipeline, J = position of the tile inside its pair:
+// tile J = (key half J/2, query half J%2).  Issues, alternating, the 4 MFMAs of
+// the S tile J+1 and the 4 MFMAs that add tile J-1 to O, and behind each the
+// vector work of one eighth of the weights of tile J, skewed by one slot
+// (fma for slot k+1, exp2 for slot k, convert + row sum for slot k-1) so that
+// no instruction waits for the one before it.  With REFILL, slot r also issues
+// slab r of a K/V refill.  S tiles and P tiles are indexed by query half: the
+// tile being weighted and its neighbours in the pipeline always differ in it.
+template <int J, bool REFILL>
+__device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2],
+                                               f32x16 (&oacc)[2][2], const bf16x8 (&qf)[2][4],
+                                               const bf16x8 (&kf)[2][4],
+                                               const bf16x8 (&vf)[2][4], float c2, float neg_m,
+                                               const Refill& rf, const uint32_t (&voff)[8])
+{
+    constexpr int nt = J & 1;
+    constexpr int mt_n = ((J + 1) & 3) >> 1, nt_n = (J + 1) & 1;   // next tile: S
+    constexpr int mt_p = ((J + 3) & 3) >> 1, nt_p = (J + 3) & 1;   // previous tile: O update
+    static_assert(nt_n != nt && nt_p != nt, "pipeline neighbours use the other buffers");
+    const f32x16 zero16 = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
+                           0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    uint32_t w[8];
+    float rs0 = 0.0f, rs1 = 0.0f;
+    float f[9][2], e[8][2];
+    f[0][0] = fmaf(s[nt][0], c2, neg_m);
+    f[0][1] = fmaf(s[nt][1], c2, neg_m);
+    asm volatile("" : "+v"(f[0][0]), "+v"(f[0][1]));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int i = k >> 1;
+        if ((k & 1) == 0) {
+            s[nt_n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt_n][i], qf[nt_n][i],
+                                                              i == 0 ? zero16 : s[nt_n], 0, 0, 0);
+        } else {
+            const int dt = i & 1, h = i >> 1;
+            oacc[dt][nt_p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                vf[dt][2 * mt_p + h], p[nt_p][h], oacc[dt][nt_p], 0, 0, 0);
+        }
+        if (REFILL) {
+            if (k < 4)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rf.rsrc_a, (__attribute__((address_space(3))) void*)(rf.lds_a + k * 1024), 16,
+                    voff[k], rf.origin_a, 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rf.rsrc_b, (__attribute__((address_space(3))) void*)(rf.lds_b + (k - 4) * 1024),
+                    16, voff[k], rf.origin_b, 0, 0);
+        }
+        // exp2 of this slot's pair, fma of the next slot's, pack and row sums
+        // of the previous slot's: nothing waits for the instruction before it
+        e[k][0] = __builtin_amdgcn_exp2f(f[k][0]);
+        e[k][1] = __builtin_amdgcn_exp2f(f[k][1]);
+        if (k + 1 < 8) {
+            f[k + 1][0] = fmaf(s[nt][2 * k + 2], c2, neg_m);
+            f[k + 1][1] = fmaf(s[nt][2 * k + 3], c2, neg_m);
+        } else {
+            f[k + 1][0] = 0.0f; f[k + 1][1] = 0.0f;
+        }
+        if (k >= 1) {
+            w[k - 1] = pack_bf16_trunc(e[k - 1][0], e[k - 1][1]);
+            rs0 += e[k - 1][0];
+            rs1 += e[k - 1][1];
+        } else {
+            w[7] = 0;
+        }
+        // an empty statement that "uses" the slot's results: it keeps their
+        // producers in this slot (they would otherwise sink to the first real
+        // use, after the last MFMA); no instruction is emitted for it
+        asm volatile(""
+                     : "+v"(e[k][0]), "+v"(e[k][1]), "+v"(f[k + 1][0]), "+v"(f[k + 1][1]),
+                       "+v"(w[k >= 1 ? k - 1 : 7]), "+v"(rs0), "+v"(rs1));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    w[7] = pack_bf16_trunc(e[7][0], e[7][1]);
+    rs0 += e[7][0];
+    rs1 += e[7][1];
+    p[nt][0] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    p[nt][1] = __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7]));
+    return rs0 + rs1;
+}
 
 __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
@@ -135,8 +242,12 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd, int subs)
 {
     constexpr int D = 64;
-    __shared__ __attribute__((aligned(1024))) unsigned char k_lds[64 * 128];
-    __shared__ __attribute__((aligned(1024))) unsigned char v_lds[64 * 128];
+    // K and V tiles as two 32-key halves each; separate objects, so that reads
+    // of one half are not ordered behind gathers into another
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[32 * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[32 * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[32 * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_lds1[32 * 128];
     __shared__ int order_s[64];
 
     const int lane = threadIdx.x;
@@ -197,7 +308,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     };
 
     // byte offset (inside a block) of the 16-byte chunk this lane gathers in
-    // instruction r: tile row 8r + lane/8, global chunk = swizzle of its LDS slot
+    // slab r: tile row 8r + lane/8, global chunk = swizzle of its LDS slot
     uint32_t voff[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -212,9 +323,23 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
 
     // K(0) and V(0) go to LDS
     {
-        const uint32_t origin_0 = origin_of(block_at(0));
-        gather_tile(k_rsrc, origin_0, voff, k_lds);
-        gather_tile(v_rsrc, origin_0, voff, v_lds);
+        const uint32_t origin_0 = origin_of(i) + (uint32_t)0;
+        gather_slab<0>(k_rsrc, origin_0, voff, k_lds0);
+        gather_slab<1>(k_rsrc, origin_0, voff, k_lds0);
+        gather_slab<2>(k_rsrc, origin_0, voff, k_lds0);
+        gather_slab<3>(k_rsrc, origin_0, voff, k_lds0);
+        gather_slab<4>(k_rsrc, origin_0, voff, k_lds1);
+        gather_slab<5>(k_rsrc, origin_0, voff, k_lds1);
+        gather_slab<6>(k_rsrc, origin_0, voff, k_lds1);
+        gather_slab<7>(k_rsrc, origin_0, voff, k_lds1);
+        gather_slab<0>(v_rsrc, origin_0, voff, v_lds0);
+        gather_slab<1>(v_rsrc, origin_0, voff, v_lds0);
+        gather_slab<2>(v_rsrc, origin_0, voff, v_lds0);
+        gather_slab<3>(v_rsrc, origin_0, voff, v_lds0);
+        gather_slab<4>(v_rsrc, origin_0, voff, v_lds1);
+        gather_slab<5>(v_rsrc, origin_0, voff, v_lds1);
+        gather_slab<6>(v_rsrc, origin_0, voff, v_lds1);
+        gather_slab<7>(v_rsrc, origin_0, voff, v_lds1);
     }
 
     // Q as B operand of S^T = K Q^T: lane (query l32 + 32 nt, half) holds
@@ -264,130 +389,149 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     const int v_row_in_step = 4 * (gq >> 1) + (s16 >> 2);
     const int v_col = 16 * (gq & 1) + 4 * (s16 & 3);     // channel (before + 32 dt)
 
-    auto read_k_frags = [&](bf16x8 (&kf)[2][4]) {
+    // fragments of one 32-key half: K rows as A operands of S^T, V through the
+    // transposing read as A operands of O^T (kf[mt][ks], vf[dt][2 mt + h])
+    bf16x8 kf[2][4], vf[2][4];
+    auto read_k_half = [&](int mt, const unsigned char* lds_half) {
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int ks = 0; ks < 4; ++ks)
+            kf[mt][ks] = *(const bf16x8*)(lds_half + l32 * 128 + swz(l32, 2 * ks + half) * 16);
+    };
+    auto read_v_half = [&](int mt, const unsigned char* lds_half) {
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const int row = l32 + 32 * mt;
-                kf[mt][ks] = *(const bf16x8*)(k_lds + row * 128 + swz(row, 2 * ks + half) * 16);
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                bf16x4 part[2];
+#pragma unroll
+                for (int rd = 0; rd < 2; ++rd) {
+                    const int row = 16 * h + 8 * rd + v_row_in_step;   // inside the half
+                    const int col = v_col + 32 * dt;                   // channel, multiple of 4
+                    const unsigned char* src =
+                        lds_half + row * 128 + swz(row, col >> 3) * 16 + (col & 7) * 2;
+                    part[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, src));
+                }
+                vf[dt][2 * mt + h] =
+                    __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
             }
     };
 
-    // K(0) has landed: loads complete in order, and K(0) is older than the loads
-    // of V(0) and Q and of the selection row (8 + 8 + 1)
-    bf16x8 kf[2][4];
-    asm volatile("s_waitcnt vmcnt(17)" ::: "memory");
-    read_k_frags(kf);
-
-    // pairs: attended block cb = 0..n (visiting order), key sub-tile ct = 0..subs-1
-    int cb = 0, ct = 0;
+    // pairs: attended block cb = 0..n (visiting order), key sub-tile ct = 0..subs-1;
+    // next_origin() walks them and returns the byte origin of the following pair
+    // (past the end it repeats the last block; those gathers use null_rsrc)
     const int pairs = (n + 1) * subs;
+    int pcb = 0, pct = 0;
+    auto next_origin = [&]() -> uint32_t {
+        if (++pct == subs) { pct = 0; ++pcb; }
+        return origin_of(block_at(pcb <= n ? pcb : n)) + (uint32_t)pct * sub_stride;
+    };
+    uint32_t o1 = next_origin();                       // origin of pair c + 1
+
+    // ---- pipeline prologue: fragments of pair 0, refill of K half 0, S tile 0
+    f32x16 s[2];            // S^T tiles, by query half
+    bf16x8 p[2][2];         // P^T tiles, by query half; [h]: keys 16 h .. 16 h + 15 of the tile
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    read_k_half(0, k_lds0);
+    read_k_half(1, k_lds1);
+    read_v_half(0, v_lds0);
+    {
+        // the first step adds a zero tile to O: weights and V fragments of
+        // "tile -1" are zeros
+        const bf16x8 zero8 = __builtin_bit_cast(bf16x8, make_uint4(0u, 0u, 0u, 0u));
+        p[1][0] = zero8; p[1][1] = zero8;
+        vf[0][2] = zero8; vf[0][3] = zero8; vf[1][2] = zero8; vf[1][3] = zero8;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    {
+        const __amdgpu_buffer_rsrc_t k1 = 1 < pairs ? k_rsrc : null_rsrc;
+        gather_slab<0>(k1, o1, voff, k_lds0);
+        gather_slab<1>(k1, o1, voff, k_lds0);
+        gather_slab<2>(k1, o1, voff, k_lds0);
+        gather_slab<3>(k1, o1, voff, k_lds0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[0][ks],
+                                                       ks == 0 ? zero16 : s[0], 0, 0, 0);
+
+    // slow path of a tile whose row sums are out of range: new reference from
+    // the row maxima, rescale O and the normaliser, recompute the weights
+    auto repair = [&](int nt) -> float {
+        float mx = s[nt][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[nt][r]);
+        mx = fmaxf(mx, swap32(mx));
+        const float m_new = fmaxf(m_ref[nt], mx * c2);
+        const float alpha = __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
+        m_ref[nt] = m_new;
+        l_run[nt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+        return tile_weights(s[nt], c2, -m_new, p[nt]);
+    };
+
     for (int c = 0; c < pairs; ++c) {
-        const bool has_next = c + 1 < pairs;
-        if (++ct == subs) { ct = 0; ++cb; }           // (cb, ct) now names pair c+1
-        const uint32_t origin_next =
-            origin_of(block_at(has_next ? cb : n)) + (has_next ? ct : 0) * sub_stride;
-        const __amdgpu_buffer_rsrc_t k_next = has_next ? k_rsrc : null_rsrc;
-        const __amdgpu_buffer_rsrc_t v_next = has_next ? v_rsrc : null_rsrc;
+        const uint32_t o2 = next_origin();             // origin of pair c + 2
+        const __amdgpu_buffer_rsrc_t k1 = c + 1 < pairs ? k_rsrc : null_rsrc;
+        const __amdgpu_buffer_rsrc_t v1 = c + 1 < pairs ? v_rsrc : null_rsrc;
+        const __amdgpu_buffer_rsrc_t k2 = c + 2 < pairs ? k_rsrc : null_rsrc;
+        Refill rf;
+        float rs;
 
-        // ---- 1. S^T = K(c) Q^T, with the K(c+1) gather between the MFMAs (the
-        // K fragments are in registers, so the K tile may be overwritten)
+        // ---- step 0: weights of tile (0,0); S of (0,1); O += tile (1,1) of the
+        // previous pair.  K half 1 and V half 0 were read in the previous step
+        // 3: refill them with pair c+1.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        f32x16 sacc[2][2];   // [mt][nt]
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-                    sacc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        kf[mt][ks], qf[nt][ks], ks == 0 ? zero16 : sacc[mt][nt], 0, 0, 0);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    k_next, LDS_PTR(void, k_lds + (2 * ks + nt) * 1024), 16, voff[2 * ks + nt],
-                    origin_next, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        rf = Refill{v1, k1, o1, o1, LDS_PTR(unsigned char, v_lds0), LDS_PTR(unsigned char, k_lds1)};
+        rs = pipeline_step<0, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff);
+        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(0);
+        l_run[0] += rs;
 
-        // ---- 2. P^T = exp2(S^T c2 - m_ref) against the current reference, one
-        // query half at a time; the slow path finds a new reference from the
-        // row maxima, rescales O and the normaliser and recomputes the weights
-        bf16x8 pf[2][4];     // [nt][kk]: keys 16 kk .. 16 kk + 15
-        bf16x8 vf[2][4];     // [dt][kk]
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            float rs = softmax_weights(sacc, nt, c2, -m_ref[nt], pf);
-            if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) {
-                float mx = sacc[0][nt][0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[0][nt][r]);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[1][nt][r]);
-                mx = fmaxf(mx, swap32(mx));
-                const float m_new = fmaxf(m_ref[nt], mx * c2);
-                const float alpha = __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
-                m_ref[nt] = m_new;
-                l_run[nt] *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
-                rs = softmax_weights(sacc, nt, c2, -m_new, pf);
-            }
-            l_run[nt] += rs;
+        // ---- step 1: weights of (0,1); S of (1,0); O += tile (0,0).  K half 0
+        // of pair c+1 and V half 1 of pair c have landed (everything older than
+        // the last 8 loads): read their fragments.
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        read_k_half(0, k_lds0);
+        read_v_half(1, v_lds1);
+        rs = pipeline_step<1, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff);
+        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(1);
+        l_run[1] += rs;
 
-            if (nt == 0) {
-                // V(c) has landed (it is older than the 8 loads of the K(c+1)
-                // gather): request its fragments now that half of S is dead;
-                // they arrive while the other half's weights are computed
-                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) {
-                        bf16x4 part[2];
-#pragma unroll
-                        for (int rd = 0; rd < 2; ++rd) {
-                            const int row = 16 * kk + 8 * rd + v_row_in_step;
-                            const int col = v_col + 32 * dt;   // channel, multiple of 4
-                            const unsigned char* p =
-                                v_lds + row * 128 + swz(row, col >> 3) * 16 + (col & 7) * 2;
-                            part[rd] =
-                                __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p));
-                        }
-                        vf[dt][kk] =
-                            __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                    }
-            }
-        }
+        // ---- step 2: weights of (1,0); S of (1,1); O += tile (0,1).  Refill K
+        // half 0 with pair c+2 and V half 1 with pair c+1.
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        rf = Refill{k2, v1, o2, o1, LDS_PTR(unsigned char, k_lds0), LDS_PTR(unsigned char, v_lds1)};
+        rs = pipeline_step<2, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff);
+        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(0);
+        l_run[0] += rs;
 
-        // ---- 3. K(c+1) has landed (nothing younger is in flight): request its
-        // fragments; they arrive during the PV product
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        if (has_next) read_k_frags(kf);
+        // ---- step 3: weights of (1,1); S of tile (0,0) of pair c+1; O += tile
+        // (1,0).  K half 1 and V half 0 of pair c+1 have landed: read them.
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        read_k_half(1, k_lds1);
+        read_v_half(0, v_lds0);
+        rs = pipeline_step<3, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff);
+        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(1);
+        l_run[1] += rs;
 
-        // ---- 4. O^T += V^T P^T, with the V(c+1) gather between the MFMAs (the
-        // V fragments are in registers, so the V tile may be overwritten)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-                    oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        vf[dt][kk], pf[nt][kk], oacc[dt][nt], 0, 0, 0);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    v_next, LDS_PTR(void, v_lds + (2 * kk + nt) * 1024), 16, voff[2 * kk + nt],
-                    origin_next, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        o1 = o2;
     }
 
-    // ---- epilogue: normalise, store O rows (4 consecutive channels per store)
+    // ---- pipeline epilogue: O += tile (1,1) of the last pair
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+            oacc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][2 + h], p[1][h],
+                                                                  oacc[dt][1], 0, 0, 0);
+
+    // ---- normalise, store O rows (4 consecutive channels per store)
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const float l_tot = l_run[nt] + swap32(l_run[nt]);
-        const float inv_l = 1.0f / l_tot;
+        const float inv_l = (1.0f / (1.0f - kTruncLoss)) / l_tot;
         uint16_t* orow = out + q_tok[nt] * D;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
