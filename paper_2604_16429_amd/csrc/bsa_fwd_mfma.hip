@@ -162,12 +162,13 @@ constexpr float kSumLimit = 4096.0f;
 // no instruction waits for the one before it.  With REFILL, slot r also issues
 // slab r of a K/V refill.  S tiles and P tiles are indexed by query half: the
 // tile being weighted and its neighbours in the pipeline always differ in it.
-template <int J, bool REFILL>
+template <int J, bool REFILL, class Mid>
 __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2],
                                                f32x16 (&oacc)[2][2], const bf16x8 (&qf)[2][4],
                                                const bf16x8 (&kf)[2][4],
                                                const bf16x8 (&vf)[2][4], float c2, float neg_m,
-                                               const Refill& rf, const uint32_t (&voff)[8])
+                                               const Refill& rf, const uint32_t (&voff)[8],
+                                               Mid mid)
 {
     constexpr int nt = J & 1;
     constexpr int mt_n = ((J + 1) & 3) >> 1, nt_n = (J + 1) & 1;   // next tile: S
@@ -185,6 +186,10 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const int i = k >> 1;
+        if (k == 4) {
+            mid();     // LDS reads of a step go here: their results are two steps away
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if ((k & 1) == 0) {
             s[nt_n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt_n][i], qf[nt_n][i],
                                                               i == 0 ? zero16 : s[nt_n], 0, 0, 0);
@@ -303,17 +308,19 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     int order_v = i;
     auto block_at = [&](int c) -> int {
         if (c == 0) return i;
-        if (sorted) return __builtin_amdgcn_readlane(order_v, c);
+        if (__builtin_expect(sorted, 1)) return __builtin_amdgcn_readlane(order_v, c);
         return sel_row[c - 1];
     };
 
+    // the tile width divides 64, so it is a power of two
+    const int bw_shift = __builtin_ctz((unsigned)g.block_w);
     // byte offset (inside a block) of the 16-byte chunk this lane gathers in
     // slab r: tile row 8r + lane/8, global chunk = swizzle of its LDS slot
     uint32_t voff[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const int t = 8 * r + (lane >> 3);
-        const int rr = t / g.block_w, cc = t - rr * g.block_w;
+        const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
         voff[r] = (uint32_t)(((rr * g.grid_w + cc) * D + swz(t, lane & 7) * 8) * 2);
     }
     auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
@@ -352,7 +359,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             const int t = 64 * qsub + l32 + 32 * nt;
-            const int rr = t / g.block_w, cc = t - rr * g.block_w;
+            const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
             q_tok[nt] = tok0 + (int64_t)rr * g.grid_w + cc;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
@@ -485,35 +492,37 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         // 3: refill them with pair c+1.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         rf = Refill{v1, k1, o1, o1, LDS_PTR(unsigned char, v_lds0), LDS_PTR(unsigned char, k_lds1)};
-        rs = pipeline_step<0, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff);
-        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(0);
+        rs = pipeline_step<0, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, [] {});
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(0);
         l_run[0] += rs;
 
         // ---- step 1: weights of (0,1); S of (1,0); O += tile (0,0).  K half 0
         // of pair c+1 and V half 1 of pair c have landed (everything older than
         // the last 8 loads): read their fragments.
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        read_k_half(0, k_lds0);
-        read_v_half(1, v_lds1);
-        rs = pipeline_step<1, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff);
-        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(1);
+        rs = pipeline_step<1, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, [&] {
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            read_k_half(0, k_lds0);
+            read_v_half(1, v_lds1);
+        });
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(1);
         l_run[1] += rs;
 
         // ---- step 2: weights of (1,0); S of (1,1); O += tile (0,1).  Refill K
         // half 0 with pair c+2 and V half 1 with pair c+1.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         rf = Refill{k2, v1, o2, o1, LDS_PTR(unsigned char, k_lds0), LDS_PTR(unsigned char, v_lds1)};
-        rs = pipeline_step<2, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff);
-        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(0);
+        rs = pipeline_step<2, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, [] {});
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(0);
         l_run[0] += rs;
 
         // ---- step 3: weights of (1,1); S of tile (0,0) of pair c+1; O += tile
         // (1,0).  K half 1 and V half 0 of pair c+1 have landed: read them.
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        read_k_half(1, k_lds1);
-        read_v_half(0, v_lds0);
-        rs = pipeline_step<3, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff);
-        if (__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0) rs = repair(1);
+        rs = pipeline_step<3, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, [&] {
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            read_k_half(1, k_lds1);
+            read_v_half(0, v_lds0);
+        });
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(1);
         l_run[1] += rs;
 
         o1 = o2;
