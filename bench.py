@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE, each scaled by the same counter on a plain copy kernel of known
 # size: 2048 and 1024 bytes per count); profiles/fwd_mfma_b64_d64_config3.md.
 # None for workloads that have not been measured.
-MEASURED_FWD_TRAFFIC_BYTES = {3: 17.84e9 + 1.69e9}
+MEASURED_FWD_TRAFFIC_BYTES = {3: 17.92e9 + 1.47e9}
 
 
 def parse_args():
@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="configuration id (1-5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--with-bwd", action="store_true",
+                    help="also run the backward (selection held fixed) after the timed steps "
+                         "and report its time; it is not part of a step")
     return ap.parse_args()
 
 
@@ -162,6 +165,24 @@ def main():
             "traffic": traffic,
         },
     }
+    if args.with_bwd:
+        dout = up(problem.dout)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        ws_b = torch.empty(max(M.mosaic_bsa_workspace_bytes(prm, binding.OP_BWD), 256),
+                           dtype=torch.uint8, device=dev)
+        reps = max(2, args.steps // 4)
+        M.mosaic_bsa_bwd(prm, q, k, v, out, lse, dout, idx, dq, dk, dv, ws_b)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            M.mosaic_bsa_bwd(prm, q, k, v, out, lse, dout, idx, dq, dk, dv, ws_b)
+        e1.record()
+        torch.cuda.synchronize()
+        bwd_ms = e0.elapsed_time(e1) / reps
+        result["bwd_ms"] = bwd_ms
+        # five block products per pair against the forward's two
+        result["bwd_effective_tflops"] = 2.5 * flops / (bwd_ms * 1e-3) / 1e12
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(problem, cfg)
     print(json.dumps(result))
