@@ -118,11 +118,14 @@ extern "C" int mosaic_bsa_fwd(const mosaic_bsa_params* params, const void* q, co
         return MOSAIC_BSA_ERR_ALIGN;
 
     hipStream_t stream = (hipStream_t)hip_stream;
-    const hipError_t e =
-        bsa::fwd_mfma_supported(c.is_bf16, c.g, c.D)
-            ? bsa::launch_fwd_mfma(q, k, v, sel_idx, out, lse, c.g, c.D, c.BH, stream)
-            : bsa::launch_fwd_generic(c.is_bf16, q, k, v, sel_idx, out, lse, c.g, c.D, c.BH,
-                                      stream);
+    hipError_t e;
+    if (bsa::fwd_mfma_supported(c.is_bf16, c.g, c.D))
+        e = bsa::launch_fwd_mfma(q, k, v, sel_idx, out, lse, c.g, c.D, c.BH, stream);
+    else if (bsa::fwd_mfma_d128_supported(c.is_bf16, c.g, c.D))
+        e = bsa::launch_fwd_mfma_d128(q, k, v, sel_idx, out, lse, c.g, c.BH, stream);
+    else
+        e = bsa::launch_fwd_generic(c.is_bf16, q, k, v, sel_idx, out, lse, c.g, c.D, c.BH,
+                                    stream);
     return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
 }
 

@@ -29,6 +29,13 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const in
                            void* out, float* lse, const Geom& g, int D, int64_t BH,
                            hipStream_t stream);
 
+// bf16 MFMA forward for head dim 128 (query blocks of 128 tokens, one workgroup
+// of four wavefronts each, K/V tiles shared through LDS).
+bool fwd_mfma_d128_supported(bool is_bf16, const Geom& g, int D);
+hipError_t launch_fwd_mfma_d128(const void* q, const void* k, const void* v,
+                                const int32_t* sel_idx, void* out, float* lse, const Geom& g,
+                                int64_t BH, hipStream_t stream);
+
 // Backward with the selection fixed; `delta` is fp32 scratch of B*heads*N floats.
 hipError_t launch_bwd(bool is_bf16, const void* q, const void* k, const void* v, const void* out,
                       const float* lse, const void* dout, const int32_t* sel_idx, void* dq,
