@@ -96,6 +96,32 @@ def test_mfma_tile_shapes(G, oracle, H, W, bh, bw, n):
     full_parity(G, oracle, cfg, q, k, v)
 
 
+@pytest.mark.parametrize("H,W,bh,bw,n", [
+    (32, 64, 8, 16, 4),      # the gradient configuration's tile
+    (32, 64, 4, 32, 0),      # block-diagonal
+    (32, 64, 16, 8, 15),     # n = m - 1: dense attention
+    (16, 128, 2, 64, 3),
+    (64, 32, 32, 4, 5),      # 4-token load slabs, the narrowest supported tile
+    (8, 64, 8, 16, 1),       # one row of tiles
+])
+def test_mfma_d128_tile_shapes(G, oracle, H, W, bh, bw, n):
+    """bf16, D = 128, tiles of 128 tokens (four-wavefront matrix-core kernel)."""
+    cfg = shape_ns(2, 2, H, W, bh, bw, 128, n, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 700 + bh + bw))
+    full_parity(G, oracle, cfg, q, k, v)
+
+
+def test_mfma_d128_is_deterministic_and_order_invariant(G, oracle):
+    cfg = shape_ns(1, 2, 32, 64, 8, 16, 128, 5, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 77))
+    idx = oracle.select(oracle.shape_of(cfg), q, k)
+    o1, l1 = G.gpu_fwd(cfg, q, k, v, idx)
+    o2, l2 = G.gpu_fwd(cfg, q, k, v, idx)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    o3, _ = G.gpu_fwd(cfg, q, k, v, idx[..., ::-1].copy())
+    assert np.abs(o3 - o1).max() <= 2e-2
+
+
 def test_config4_quarter_degree_reduced(G, oracle):
     """The 0.25 degree configuration's tiles, head dim and n on a reduced grid
     (full forward against the oracle), seeded smooth fields."""
