@@ -119,6 +119,9 @@ __device__ __forceinline__ uint32_t wave_umin(uint32_t v)
     return min(min(a, b), min(c, d));
 }
 
+// Candidates a lane keeps in registers in the top-n phase (m <= 64 * kSlots).
+constexpr int kSlots = 8;
+
 // One workgroup of 256 threads ranks G consecutive query blocks of one
 // (batch, head).
 //   phase 1: thread t owns key block j = chunk*256 + t, holds kbar_j in
@@ -184,6 +187,46 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
     for (int r = wave; r < rows; r += (int)(blockDim.x >> 6)) {
         uint32_t* keys = key_s + r * m;
         int32_t* dst = sel_idx + ((bh_idx * m) + i0 + r) * n;
+        if (m <= 64 * kSlots) {
+            // Candidates j == lane (mod 64) live in registers, slot t = j / 64.
+            // Per round: wave-wide max of the lanes' best keys; the winner is
+            // the lane holding it (the smallest block index among them when
+            // several do, which only happens for exactly equal scores); that
+            // lane clears the slot and re-derives its best.
+            uint32_t kreg[kSlots];
+#pragma unroll
+            for (int t = 0; t < kSlots; ++t) {
+                const int j = lane + 64 * t;
+                kreg[t] = j < m ? keys[j] : 0u;
+            }
+            auto lane_best = [&](uint32_t& best, uint32_t& best_j) {
+                best = kreg[0]; uint32_t slot = 0;
+#pragma unroll
+                for (int t = 1; t < kSlots; ++t)
+                    if (kreg[t] > best) { best = kreg[t]; slot = (uint32_t)t; }
+                best_j = best ? (uint32_t)lane + 64u * slot : 0xffffffffu;
+            };
+            uint32_t best, best_j;
+            lane_best(best, best_j);
+            for (int t = 0; t < n; ++t) {
+                const uint32_t top = wave_umax(best);
+                const uint64_t holders = __builtin_amdgcn_ballot_w64(best == top);
+                uint32_t win;
+                if (__builtin_expect(__builtin_popcountll(holders) == 1, 1))
+                    win = __builtin_amdgcn_readlane(best_j, (int)__builtin_ctzll(holders));
+                else
+                    win = wave_umin(best == top ? best_j : 0xffffffffu);
+                if (lane == 0) dst[t] = (int32_t)win;
+                if ((win & 63u) == (uint32_t)lane) {
+                    const uint32_t slot = win >> 6;
+#pragma unroll
+                    for (int u = 0; u < kSlots; ++u)
+                        if (slot == (uint32_t)u) kreg[u] = 0u;
+                    lane_best(best, best_j);
+                }
+            }
+            continue;
+        }
         uint32_t best = 0u, best_j = 0xffffffffu;
         for (int j = lane; j < m; j += 64) {
             const uint32_t u = keys[j];
