@@ -63,8 +63,15 @@
 
 namespace bsa {
 
-// 16-byte chunk swizzle of a 128-byte LDS row (8 chunks per row).
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+// 16-byte chunk swizzle of a 128-byte LDS row (8 chunks per row).  The K
+// fragment read takes the same chunk of 8 consecutive rows per 128 bytes of
+// bank width, the transposing V read 32 bytes (a chunk pair) of 4 consecutive
+// rows: the row's XOR mask is a bijection of row % 8 whose upper two bits
+// differ over any 4 aligned rows.
+__device__ __forceinline__ int swz(int row, int chunk)
+{
+    return chunk ^ (((row & 3) << 1) | ((row >> 2) & 1));
+}
 
 // Gather one 32-token x 64-channel bf16 half tile into LDS (4 KiB, rows
 // swizzled) with buffer loads that write LDS directly.  A whole 64-token tile
@@ -100,13 +107,13 @@ struct Refill {
 // no instruction waits for the one before it.  With REFILL, slot r also issues
 // slab r of a K/V refill.  S tiles and P tiles are indexed by query half: the
 // tile being weighted and its neighbours in the pipeline always differ in it.
-template <int J, bool REFILL, class Mid>
+template <int J, bool REFILL, int NW, class Mid>
 __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2],
                                                f32x16 (&oacc)[2][2], const bf16x8 (&qf)[2][4],
                                                const bf16x8 (&kf)[2][4],
                                                const bf16x8 (&vf)[2][4], float c2, float neg_m,
                                                const Refill& rf, const uint32_t (&voff)[8],
-                                               Mid mid)
+                                               int wave, Mid mid)
 {
     constexpr int nt = J & 1;
     constexpr int mt_n = ((J + 1) & 3) >> 1, nt_n = (J + 1) & 1;   // next tile: S
@@ -136,7 +143,9 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
             oacc[dt][nt_p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 vf[dt][2 * mt_p + h], p[nt_p][h], oacc[dt][nt_p], 0, 0, 0);
         }
-        if (REFILL) {
+        if (REFILL && (NW == 1 || (k & (NW - 1)) == wave)) {
+            // (the wavefronts of a workgroup share the refill: slot k belongs
+            // to wavefront k mod NW)
             if (k < 4)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     rf.rsrc_a, (__attribute__((address_space(3))) void*)(rf.lds_a + k * 1024), 16,
@@ -179,21 +188,38 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
     return rs0 + rs1;
 }
 
-__global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
+// The kernel body for workgroups of NW wavefronts.  NW consecutive 64-query
+// sub-blocks of one query block attend to the same K/V tiles, so with NW > 1
+// the tiles in LDS are shared: the loads of a refill are split between the
+// wavefronts and each group of half tiles takes two workgroup barriers per
+// pair, "all reads done" before its refill is issued and "all loads landed"
+// (each wavefront waits for its own loads first) before it is read again.
+template <int NW>
+__device__ __forceinline__ void fwd_mfma_d64_body(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
-    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd, int subs)
+    uint16_t* __restrict__ out, float* __restrict__ lse, const Geom& g, int64_t slices_xcd,
+    int subs)
 {
     constexpr int D = 64;
+    static_assert(NW == 1 || NW == 2 || NW == 4, "8 loads per refill step, split between waves");
+    auto wg_barrier = [] { if (NW > 1) __builtin_amdgcn_s_barrier(); };
+    // all but this wavefront's loads of the most recent refill step (8 / NW)
+    auto wait_older_loads = [] {
+        if (NW == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (NW == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (NW == 4) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    };
     // K and V tiles as two 32-key halves each; separate objects, so that reads
     // of one half are not ordered behind gathers into another
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[32 * 128];
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[32 * 128];
     __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[32 * 128];
     __shared__ __attribute__((aligned(1024))) unsigned char v_lds1[32 * 128];
-    __shared__ int order_s[64];
+    __shared__ int order_s[NW][64];
 
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = NW == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int n = g.n_select;
 
@@ -202,12 +228,14 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     // to XCDs whole (slice s runs on XCD s % 8, its query blocks back to back),
     // so the K/V tiles a slice's query blocks share are fetched into one L2
     // instead of eight.  The last BH % 8 slices use the plain linear order.
-    // A work item is one sub-block of 64 queries: item = block * subs + sub.
+    // A work item is NW consecutive sub-blocks of 64 queries of one query
+    // block (NW divides subs): item = block * (subs / NW) + group.
     int i, qsub;
     int64_t bh_idx;
     {
         const int64_t w = blockIdx.x;
-        const int64_t per_slice = (int64_t)g.n_blocks * subs;
+        const int groups = subs / NW;
+        const int64_t per_slice = (int64_t)g.n_blocks * groups;
         int64_t item;
         if (w < slices_xcd * per_slice) {
             const int64_t seq = w >> 3;
@@ -217,8 +245,8 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
             bh_idx = w / per_slice;
             item = w % per_slice;
         }
-        i = (int)(item / subs);
-        qsub = (int)(item - (int64_t)i * subs);
+        i = (int)(item / groups);
+        qsub = (int)(item - (int64_t)i * groups) * NW + wave;
     }
     // byte distance between consecutive 64-token sub-tiles of a block: 64/bw
     // grid rows (the tile width divides 64)
@@ -269,22 +297,26 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     // K(0) and V(0) go to LDS
     {
         const uint32_t origin_0 = origin_of(i) + (uint32_t)0;
-        gather_slab<0>(k_rsrc, origin_0, voff, k_lds0);
-        gather_slab<1>(k_rsrc, origin_0, voff, k_lds0);
-        gather_slab<2>(k_rsrc, origin_0, voff, k_lds0);
-        gather_slab<3>(k_rsrc, origin_0, voff, k_lds0);
-        gather_slab<4>(k_rsrc, origin_0, voff, k_lds1);
-        gather_slab<5>(k_rsrc, origin_0, voff, k_lds1);
-        gather_slab<6>(k_rsrc, origin_0, voff, k_lds1);
-        gather_slab<7>(k_rsrc, origin_0, voff, k_lds1);
-        gather_slab<0>(v_rsrc, origin_0, voff, v_lds0);
-        gather_slab<1>(v_rsrc, origin_0, voff, v_lds0);
-        gather_slab<2>(v_rsrc, origin_0, voff, v_lds0);
-        gather_slab<3>(v_rsrc, origin_0, voff, v_lds0);
-        gather_slab<4>(v_rsrc, origin_0, voff, v_lds1);
-        gather_slab<5>(v_rsrc, origin_0, voff, v_lds1);
-        gather_slab<6>(v_rsrc, origin_0, voff, v_lds1);
-        gather_slab<7>(v_rsrc, origin_0, voff, v_lds1);
+        // (split between the wavefronts of the workgroup: slab r belongs to
+        // wavefront r mod NW)
+#define BSA_GATHER_MINE(R, RSRC, ORIGIN, LDS) \
+    if (NW == 1 || ((R) & (NW - 1)) == wave) gather_slab<R>(RSRC, ORIGIN, voff, LDS)
+        BSA_GATHER_MINE(0, k_rsrc, origin_0, k_lds0);
+        BSA_GATHER_MINE(1, k_rsrc, origin_0, k_lds0);
+        BSA_GATHER_MINE(2, k_rsrc, origin_0, k_lds0);
+        BSA_GATHER_MINE(3, k_rsrc, origin_0, k_lds0);
+        BSA_GATHER_MINE(4, k_rsrc, origin_0, k_lds1);
+        BSA_GATHER_MINE(5, k_rsrc, origin_0, k_lds1);
+        BSA_GATHER_MINE(6, k_rsrc, origin_0, k_lds1);
+        BSA_GATHER_MINE(7, k_rsrc, origin_0, k_lds1);
+        BSA_GATHER_MINE(0, v_rsrc, origin_0, v_lds0);
+        BSA_GATHER_MINE(1, v_rsrc, origin_0, v_lds0);
+        BSA_GATHER_MINE(2, v_rsrc, origin_0, v_lds0);
+        BSA_GATHER_MINE(3, v_rsrc, origin_0, v_lds0);
+        BSA_GATHER_MINE(4, v_rsrc, origin_0, v_lds1);
+        BSA_GATHER_MINE(5, v_rsrc, origin_0, v_lds1);
+        BSA_GATHER_MINE(6, v_rsrc, origin_0, v_lds1);
+        BSA_GATHER_MINE(7, v_rsrc, origin_0, v_lds1);
     }
 
     // Q as B operand of S^T = K Q^T: lane (query l32 + 32 nt, half) holds
@@ -311,9 +343,9 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         int rank = 1;
         for (int t = 1; t <= n; ++t)
             rank += __builtin_amdgcn_readlane(mine, t) < mine ? 1 : 0;
-        if (lane >= 1 && lane <= n) order_s[rank] = mine;
+        if (lane >= 1 && lane <= n) order_s[wave][rank] = mine;
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        order_v = order_s[lane];
+        order_v = order_s[wave][lane];
     }
 
     const float c2 = g.scale * 1.4426950408889634f;
@@ -376,6 +408,7 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     f32x16 s[2];            // S^T tiles, by query half
     bf16x8 p[2][2];         // P^T tiles, by query half; [h]: keys 16 h .. 16 h + 15 of the tile
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wg_barrier();                                      // pair 0's tiles have landed
     read_k_half(0, k_lds0);
     read_k_half(1, k_lds1);
     read_v_half(0, v_lds0);
@@ -387,13 +420,15 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         vf[0][2] = zero8; vf[0][3] = zero8; vf[1][2] = zero8; vf[1][3] = zero8;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    wg_barrier();                                      // everyone has read K half 0
     {
         const __amdgpu_buffer_rsrc_t k1 = 1 < pairs ? k_rsrc : null_rsrc;
-        gather_slab<0>(k1, o1, voff, k_lds0);
-        gather_slab<1>(k1, o1, voff, k_lds0);
-        gather_slab<2>(k1, o1, voff, k_lds0);
-        gather_slab<3>(k1, o1, voff, k_lds0);
+        BSA_GATHER_MINE(0, k1, o1, k_lds0);
+        BSA_GATHER_MINE(1, k1, o1, k_lds0);
+        BSA_GATHER_MINE(2, k1, o1, k_lds0);
+        BSA_GATHER_MINE(3, k1, o1, k_lds0);
     }
+#undef BSA_GATHER_MINE
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[0][ks],
@@ -429,16 +464,19 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         // previous pair.  K half 1 and V half 0 were read in the previous step
         // 3: refill them with pair c+1.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        wg_barrier();
         rf = Refill{v1, k1, o1, o1, LDS_PTR(unsigned char, v_lds0), LDS_PTR(unsigned char, k_lds1)};
-        rs = pipeline_step<0, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, [] {});
+        rs = pipeline_step<0, true, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, wave,
+                                        [] {});
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(0);
         l_run[0] += rs;
 
         // ---- step 1: weights of (0,1); S of (1,0); O += tile (0,0).  K half 0
         // of pair c+1 and V half 1 of pair c have landed (everything older than
         // the last 8 loads): read their fragments.
-        rs = pipeline_step<1, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, [&] {
-            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        rs = pipeline_step<1, false, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, wave, [&] {
+            wait_older_loads();
+            wg_barrier();
             read_k_half(0, k_lds0);
             read_v_half(1, v_lds1);
         });
@@ -448,15 +486,18 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
         // ---- step 2: weights of (1,0); S of (1,1); O += tile (0,1).  Refill K
         // half 0 with pair c+2 and V half 1 with pair c+1.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        wg_barrier();
         rf = Refill{k2, v1, o2, o1, LDS_PTR(unsigned char, k_lds0), LDS_PTR(unsigned char, v_lds1)};
-        rs = pipeline_step<2, true>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, [] {});
+        rs = pipeline_step<2, true, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, wave,
+                                        [] {});
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(0);
         l_run[0] += rs;
 
         // ---- step 3: weights of (1,1); S of tile (0,0) of pair c+1; O += tile
         // (1,0).  K half 1 and V half 0 of pair c+1 have landed: read them.
-        rs = pipeline_step<3, false>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, [&] {
-            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        rs = pipeline_step<3, false, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, wave, [&] {
+            wait_older_loads();
+            wg_barrier();
             read_k_half(1, k_lds1);
             read_v_half(0, v_lds0);
         });
@@ -497,6 +538,21 @@ __global__ __launch_bounds__(64, 2) void fwd_mfma_b64_d64_kernel(
     }
 }
 
+// One kernel per workgroup size (plain functions: the body is the template).
+#define BSA_FWD_D64_KERNEL(NAME, NW)                                                              \
+    __global__ __launch_bounds__(64 * NW, 2) void NAME(                                           \
+        const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,                           \
+        const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,                      \
+        uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd,          \
+        int subs)                                                                                 \
+    {                                                                                             \
+        fwd_mfma_d64_body<NW>(q, k, v, sel_idx, out, lse, g, slices_xcd, subs);                   \
+    }
+BSA_FWD_D64_KERNEL(fwd_mfma_b64_d64_kernel, 1)
+BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg2_kernel, 2)
+BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg4_kernel, 4)
+#undef BSA_FWD_D64_KERNEL
+
 bool fwd_mfma_supported(bool is_bf16, const Geom& g, int D)
 {
     // tiles of 64*T tokens whose width divides 64: every 64-token sub-tile is
@@ -513,10 +569,15 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const in
 {
     (void)D;
     const int subs = g.block_tokens / 64;
-    dim3 grid((unsigned)(BH * g.n_blocks * subs));
-    hipLaunchKernelGGL(fwd_mfma_b64_d64_kernel, grid, dim3(64), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
-                       BH - BH % 8, subs);
+    // the sub-blocks of a query block share their K/V tiles in LDS, four or two
+    // to a workgroup when the count allows
+    const int nw = subs % 4 == 0 ? 4 : subs % 2 == 0 ? 2 : 1;
+    dim3 grid((unsigned)(BH * g.n_blocks * (subs / nw)));
+    auto kernel = nw == 4 ? fwd_mfma_d64_wg4_kernel
+                  : nw == 2 ? fwd_mfma_d64_wg2_kernel : fwd_mfma_b64_d64_kernel;
+    kernel<<<grid, dim3(64 * nw), 0, stream>>>((const uint16_t*)q, (const uint16_t*)k,
+                                               (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
+                                               (int64_t)(BH - BH % 8), subs);
     return hipGetLastError();
 }
 

@@ -31,11 +31,13 @@
 //
 // LDS: K and V as two 32-key halves each (4 x 8 KiB).  A half is read once per
 // pair by every wavefront and then refilled with the same half of the next
-// sub-tile; the 8 loads of a half are split between the wavefronts.  Two
-// groups of halves, {K half 0, V half 0} and {K half 1, V half 1}, each take
-// two workgroup barriers per pair: "all reads done" before the refill is
-// issued and "all loads landed" (each wavefront waits for its own loads first)
-// before the next read.
+// sub-tile; the 8 loads of a half are split between the wavefronts.  A step
+// has two workgroup barriers: at its start "all reads of the K half read in the
+// previous step are done", after which that K half is refilled; after its S
+// MFMAs "the halves refilled a step ago have landed" (each wavefront waits for
+// its own loads first) and "all reads of the V half read at the end of the
+// previous step are done", after which the K half is read and that V half is
+// refilled.
 #include <type_traits>
 
 #include "bsa_device.h"
@@ -50,9 +52,15 @@ constexpr int D = 128;
 constexpr int ROW_BYTES = D * 2;          // one token row of K or V in LDS
 constexpr int HALF_BYTES = 32 * ROW_BYTES;
 
-// 16-byte chunk swizzle of a 256-byte LDS row (16 chunks per row): rows that
-// are read together (8 consecutive rows, same chunk) land in different banks.
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
+// 16-byte chunk swizzle of a 256-byte LDS row (16 chunks per row).  The K
+// fragment read takes the same chunk of 8 consecutive rows per 128 bytes of
+// bank width, the transposing V read 32 bytes (a chunk pair) of 4 consecutive
+// rows: the row's XOR mask is a bijection of row % 8 whose upper two bits
+// differ over any 4 aligned rows.
+__device__ __forceinline__ int swz(int row, int chunk)
+{
+    return chunk ^ (((row & 3) << 1) | ((row >> 2) & 1));
+}
 
 }  // namespace d128
 
@@ -123,7 +131,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
 
     // Gather geometry.  One load moves 1 KiB = 4 token rows; lane l fills LDS
     // chunk l of that slab, i.e. row l/16, swizzled chunk l%16, so it fetches
-    // global chunk (l%16) ^ (row & 7).  The tile width is a power of two >= 4,
+    // the global chunk that swizzles to l%16 (the swizzle is an involution).  The tile width is a power of two >= 4,
     // so the 4 tokens of a slab are contiguous in memory: a per-lane offset
     // (two variants, by the parity of the slab inside the half) plus a
     // wave-uniform offset of the slab's first token.
@@ -132,7 +140,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
         const int row = 4 * par + (lane >> 4);
-        voff_par[par] = (uint32_t)((lane >> 4) * ROW_BYTES + (((lane & 15) ^ (row & 7)) * 16));
+        voff_par[par] = (uint32_t)((lane >> 4) * ROW_BYTES + swz(row, lane & 15) * 16);
     }
     auto slab_offset = [&](int hh, int slab) -> uint32_t {   // first token of a slab, bytes
         const int t0 = 32 * hh + 4 * slab;
@@ -282,6 +290,14 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         return tile_weights(s[par], c2, -m_new, p[par]);
     };
 
+    // everything but this wavefront's most recent refill share has landed, and
+    // its LDS reads are done
+    auto wait_older_loads = [] {
+        if (LOADS == 1) asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)" ::: "memory");
+        if (LOADS == 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");
+        if (LOADS == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+    };
+
     // One step: tile J of the pair (key half J).  S of the next tile from the
     // K fragments in registers (8 MFMAs), then the K fragments of the tile
     // after that are requested from k_next_lds; O += previous tile with the V
@@ -374,18 +390,22 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         rs = step(
             std::integral_constant<int, 0>{},
             [&] {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                // K upper half: its fragment reads are older than the 16 V
+                // reads just issued, so "at most 15 outstanding" covers them
+                // (LDS operations complete in order; not so with a scalar
+                // load of the selection row in flight)
+                if (sorted) asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
+                else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 refill_half(k1, o1, 1, k_lds1);
-                refill_half(v_rsrc, o0, 1, v_lds1);     // pair c itself always exists
             },
             [&] {
                 // own share of the lower-half refills has landed (everything
-                // older than the 2*LOADS loads just issued), then everyone's
-                if (LOADS == 1) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-                if (LOADS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                if (LOADS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                // older than the K loads just issued), own V reads are done;
+                // then everyone's.  The V upper half can be refilled now.
+                wait_older_loads();
                 __builtin_amdgcn_s_barrier();
+                refill_half(v_rsrc, o0, 1, v_lds1);     // pair c itself always exists
             },
             k_lds0, v_lds0);
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0))
@@ -400,16 +420,15 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         rs = step(
             std::integral_constant<int, 1>{},
             [&] {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (sorted) asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
+                else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 refill_half(k2, o2, 0, k_lds0);
-                refill_half(v1, o1, 0, v_lds0);
             },
             [&] {
-                if (LOADS == 1) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-                if (LOADS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                if (LOADS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                wait_older_loads();
                 __builtin_amdgcn_s_barrier();
+                refill_half(v1, o1, 0, v_lds0);
             },
             k_lds1, v_lds1);
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0))
