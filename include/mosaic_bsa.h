@@ -128,8 +128,8 @@ int mosaic_bsa_fwd(const mosaic_bsa_params *params, const void *q, const void *k
  *   dq, dk, dv          out  device, [B, heads, N, D], element type of q
  *   workspace                device scratch of
  *                            mosaic_bsa_workspace_bytes(.., OP_BWD) bytes; on
- *                            return it holds delta_l = dout_l . out_l, fp32
- *                            [B, heads, N].
+ *                            return its first half holds delta_l = dout_l . out_l,
+ *                            fp32 [B, heads, N] (the second half is scratch).
  * dk/dv of a key block are reduced over the query blocks that attend to it in
  * a fixed order (no floating-point atomics): results are run-to-run identical.
  */

@@ -64,7 +64,8 @@ size_t select_workspace(const Checked& c)
 
 size_t bwd_workspace(const Checked& c)
 {
-    return align_up((size_t)c.BH * (size_t)c.g.n_tokens * sizeof(float));   // delta
+    // delta, then lse * log2(e) (the second half is used by the matrix-core path)
+    return 2 * align_up((size_t)c.BH * (size_t)c.g.n_tokens * sizeof(float));
 }
 
 }  // namespace
@@ -144,8 +145,14 @@ extern "C" int mosaic_bsa_bwd(const mosaic_bsa_params* params, const void* q, co
     if (!workspace || workspace_bytes < bwd_workspace(c)) return MOSAIC_BSA_ERR_WORKSPACE;
 
     hipStream_t stream = (hipStream_t)hip_stream;
-    const hipError_t e = bsa::launch_bwd(c.is_bf16, q, k, v, out, lse, dout, sel_idx, dq, dk, dv,
-                                         (float*)workspace, c.g, c.D, c.BH, stream);
+    float* delta = (float*)workspace;
+    float* lse2 = (float*)((char*)workspace + bwd_workspace(c) / 2);
+    const hipError_t e =
+        bsa::bwd_mfma_supported(c.is_bf16, c.g, c.D)
+            ? bsa::launch_bwd_mfma(q, k, v, out, lse, dout, sel_idx, dq, dk, dv, delta, lse2, c.g,
+                                   c.D, c.BH, stream)
+            : bsa::launch_bwd(c.is_bf16, q, k, v, out, lse, dout, sel_idx, dq, dk, dv, delta, c.g,
+                              c.D, c.BH, stream);
     return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
 }
 

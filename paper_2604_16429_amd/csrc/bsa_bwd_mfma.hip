@@ -1,0 +1,611 @@
+// Backward of the block-sparse attention on the gfx950 matrix cores (bf16 MFMA,
+// fp32 accumulation), selection held fixed: no gradient flows through the
+// top-n choice (Appendix "Block-sparse attention implementation").
+//
+// With P the attention weights of the forward pass, recomputed from the stored
+// log-sum-exp as P = exp(scale * q.k - lse), and delta_l = dO_l . O_l:
+//   dV_t = sum_l P_lt dO_l          dP_lt = dO_l . v_t
+//   dS_lt = P_lt (dP_lt - delta_l)
+//   dQ_l = scale * sum_t dS_lt k_t  dK_t = scale * sum_l dS_lt q_l
+// where t runs over the keys of the blocks query block i attends to (itself and
+// its selection) and l over the queries of the blocks that attend to t's block.
+//
+// Two kernels, both built from 32 x 32 x 16 bf16 MFMAs on 64-token tiles that
+// the wavefronts of a workgroup share through LDS (direct-to-LDS gathers,
+// double buffered, one workgroup barrier per tile):
+//   dq kernel    one workgroup per query block, a wavefront per 32 query rows,
+//                walks the attended K/V sub-tiles like the forward pass.  Per
+//                32-key tile: S^T = K Q^T and dP^T = V dO^T (a lane holds one
+//                query column, so lse and delta are per-lane scalars),
+//                dS^T in registers is the B operand of dQ^T += K^T dS^T, whose A
+//                operand comes from the transposing LDS read of the K tile.
+//   dk/dv kernel one workgroup per key/value block, a wavefront per 32 key rows
+//                (their K and V rows stay in registers as B operands).  It
+//                lists, in ascending order, the query blocks that attend to
+//                its block (the paper's "query blocks connected to a key/value
+//                block"; no stored reverse map, no floating-point atomics: the
+//                list order fixes the summation order) and walks their Q/dO
+//                sub-tiles.  Per 32-query tile: S = Q K^T and dP = dO V^T (rows
+//                are queries now: lse and delta come from LDS per row), and
+//                dV^T += dO^T P, dK^T += Q^T dS with the transposing LDS read
+//                of the dO / Q tile.  For head dim 128 the two accumulators do
+//                not fit next to the operands, so dV and dK are two passes.
+#include "bsa_device.h"
+#include "bsa_launch.h"
+#include "bsa_mfma_common.h"
+
+namespace bsa {
+
+namespace bwdm {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// 16-byte chunk swizzle of an LDS row (8 or 16 chunks): a bijection of row % 8
+// whose upper two bits differ over 4 aligned rows (row-fragment reads take the
+// same chunk of 8 consecutive rows, transposing reads a chunk pair of 4 rows).
+__device__ __forceinline__ int swz(int row, int chunk)
+{
+    return chunk ^ (((row & 3) << 1) | ((row >> 2) & 1));
+}
+
+// Geometry of 64-token x D tiles gathered into LDS by a workgroup of NW
+// wavefronts.  A tile is SLABS loads of 1 KiB (RPS token rows each); wavefront
+// w issues slabs w, w + NW, ...; lane l fills LDS chunk l of the slab, i.e. row
+// l / LPR, swizzled chunk l % LPR, and therefore fetches the global chunk that
+// swizzles to that slot.
+template <int D, int NW>
+struct TileIO {
+    static constexpr int ROW_BYTES = D * 2;
+    static constexpr int TILE_BYTES = 64 * ROW_BYTES;
+    static constexpr int SLABS = TILE_BYTES / 1024;
+    static constexpr int RPS = 1024 / ROW_BYTES;       // token rows per slab
+    static constexpr int LPR = ROW_BYTES / 16;         // lanes per token row
+    static constexpr int MINE = SLABS / NW;            // slabs per wavefront
+    static_assert(SLABS % NW == 0, "slabs split evenly between wavefronts");
+
+    uint32_t voff[MINE];        // byte offset of this lane's chunk inside a sub-tile
+    uint32_t tok_off;           // byte offset (fp32 rows) of token `lane` of a sub-tile
+    int wave;
+
+    __device__ __forceinline__ void init(const Geom& g, int lane, int wave_)
+    {
+        wave = wave_;
+        const int bw_shift = __builtin_ctz((unsigned)g.block_w);
+#pragma unroll
+        for (int j = 0; j < MINE; ++j) {
+            const int slab = wave + j * NW;
+            const int t = RPS * slab + lane / LPR;                    // token row 0..63
+            const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
+            voff[j] = (uint32_t)((rr * g.grid_w + cc) * ROW_BYTES + swz(t, lane % LPR) * 16);
+        }
+        const int rr = lane >> bw_shift, cc = lane & (g.block_w - 1);
+        tok_off = (uint32_t)((rr * g.grid_w + cc) * 4);
+    }
+    // this wavefront's share of one tile (origin: byte offset of the sub-tile's
+    // first token in a [N, D] bf16 slice)
+    __device__ __forceinline__ void gather(__amdgpu_buffer_rsrc_t rsrc, uint32_t origin,
+                                           unsigned char* lds_tile) const
+    {
+#pragma unroll
+        for (int j = 0; j < MINE; ++j) {
+            const int slab = wave + j * NW;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds_tile + slab * 1024), 16,
+                                                     voff[j], origin, 0, 0);
+        }
+    }
+    // 64 fp32 values (one per token of the sub-tile) from a [N] fp32 slice;
+    // origin_tok: index of the sub-tile's first token
+    __device__ __forceinline__ void gather_f32(__amdgpu_buffer_rsrc_t rsrc, uint32_t origin_tok,
+                                               float* lds_vec) const
+    {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds_vec), 4, tok_off,
+                                                 origin_tok * 4u, 0, 0);
+    }
+};
+
+// Row fragment: lane (l32, half) reads channels 16 ks + 8 half .. + 7 of tile
+// row row0 + l32 (A operand "rows x channels", or B operand of the same shape).
+template <int D>
+__device__ __forceinline__ bf16x8 row_frag(const unsigned char* tile, int row0, int ks, int l32,
+                                           int half)
+{
+    const int row = row0 + l32;
+    return *(const bf16x8*)(tile + row * (D * 2) + swz(row, 2 * ks + half) * 16);
+}
+
+// Transposed fragment: A operand "channels 32 dt .. x tile rows row0 .. row0+15"
+// through the transposing LDS read (source lane s of 16-lane group gq supplies
+// 8 bytes of row row0 + 8 rd + 4 (gq/2) + s/4, channel 16 (gq%2) + 4 (s%4) + 32 dt).
+template <int D>
+__device__ __forceinline__ bf16x8 trans_frag(const unsigned char* tile, int row0, int dt,
+                                             int lane)
+{
+    const int s16 = lane & 15, gq = lane >> 4;
+    const int col = 16 * (gq & 1) + 4 * (s16 & 3) + 32 * dt;
+    bf16x4 part[2];
+#pragma unroll
+    for (int rd = 0; rd < 2; ++rd) {
+        const int row = row0 + 8 * rd + 4 * (gq >> 1) + (s16 >> 2);
+        const unsigned char* src = tile + row * (D * 2) + swz(row, col >> 3) * 16 + (col & 7) * 2;
+        part[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, src));
+    }
+    return __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// 16 fp32 accumulator values -> two bf16 B operands (round to nearest even)
+__device__ __forceinline__ void pack_tile(const f32x16& x, bf16x8 (&b)[2])
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+        b[h] = __builtin_bit_cast(
+            bf16x8, make_uint4(pack_bf16(x[8 * h + 0], x[8 * h + 1]),
+                               pack_bf16(x[8 * h + 2], x[8 * h + 3]),
+                               pack_bf16(x[8 * h + 4], x[8 * h + 5]),
+                               pack_bf16(x[8 * h + 6], x[8 * h + 7])));
+}
+
+// Store one accumulator tile (rows = channels 32 dt .., this lane's column =
+// one token row) scaled by f: 4 consecutive channels per 8-byte store.
+__device__ __forceinline__ void store_tile(uint16_t* row_ptr, int dt, int half, const f32x16& a,
+                                           float f)
+{
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+        const int d = 32 * dt + 8 * r4 + 4 * half;
+        uint2 w;
+        w.x = pack_bf16(a[4 * r4] * f, a[4 * r4 + 1] * f);
+        w.y = pack_bf16(a[4 * r4 + 2] * f, a[4 * r4 + 3] * f);
+        *(uint2*)(row_ptr + d) = w;
+    }
+}
+
+__device__ __forceinline__ f32x16 zero_tile()
+{
+    const f32x16 z = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
+                      0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    return z;
+}
+
+// ---------------------------------------------------------------------------
+// dQ
+// ---------------------------------------------------------------------------
+template <int D, int NW>
+__device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
+                                        const uint16_t* __restrict__ k,
+                                        const uint16_t* __restrict__ v,
+                                        const uint16_t* __restrict__ dout,
+                                        const float* __restrict__ lse2,
+                                        const float* __restrict__ delta,
+                                        const int32_t* __restrict__ sel_idx,
+                                        uint16_t* __restrict__ dq, const Geom& g,
+                                        int64_t slices_xcd)
+{
+    constexpr int KS = D / 16, DT = D / 32;
+    using IO = TileIO<D, NW>;
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds[2][IO::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_lds[2][IO::TILE_BYTES];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int n = g.n_select;
+    const int subs = g.block_tokens / 64;
+
+    // workgroup -> (slice, query block), slices dealt to the 8 XCDs whole
+    int i;
+    int64_t bh_idx;
+    {
+        const int64_t w = blockIdx.x;
+        const int64_t per_slice = g.n_blocks;
+        if (w < slices_xcd * per_slice) {
+            const int64_t seq = w >> 3;
+            bh_idx = (seq / per_slice) * 8 + (w & 7);
+            i = (int)(seq % per_slice);
+        } else {
+            bh_idx = w / per_slice;
+            i = (int)(w % per_slice);
+        }
+    }
+    const uint32_t sub_stride = (uint32_t)((64 / g.block_w) * g.grid_w * (D * 2));
+    const int64_t base = bh_idx * g.n_tokens * D;
+    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
+    const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
+    const __amdgpu_buffer_rsrc_t k_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, slice_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(v + base), 0, slice_bytes, 0x00020000);
+
+    IO io;
+    io.init(g, lane, wave);
+    auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
+        const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
+        return (uint32_t)((br * g.block_h * g.grid_w + bc * g.block_w) * (D * 2));
+    };
+    const int pairs = (n + 1) * subs;
+    auto origin_of_pair = [&](int c) -> uint32_t {   // attended block c / subs, sub-tile c % subs
+        const int cb = c / subs, ct = c - cb * subs;
+        return origin_of(cb == 0 ? i : sel_row[cb - 1]) + (uint32_t)ct * sub_stride;
+    };
+
+    io.gather(k_rsrc, origin_of_pair(0), k_lds[0]);
+    io.gather(v_rsrc, origin_of_pair(0), v_lds[0]);
+
+    // this wavefront's 32 query rows: Q and dO as B operands, lse and delta of
+    // the lane's query column
+    bf16x8 qf[KS], dof[KS];
+    int64_t q_tok;
+    {
+        const int bw_shift = __builtin_ctz((unsigned)g.block_w);
+        const int br = i / g.blocks_per_row, bc = i - br * g.blocks_per_row;
+        const int64_t tok0 = (int64_t)br * g.block_h * g.grid_w + (int64_t)bc * g.block_w;
+        const int t = 32 * wave + l32;
+        const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
+        q_tok = tok0 + (int64_t)rr * g.grid_w + cc;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = *(const bf16x8*)(q + base + q_tok * D + 16 * ks + 8 * half);
+            dof[ks] = *(const bf16x8*)(dout + base + q_tok * D + 16 * ks + 8 * half);
+        }
+    }
+    const float neg_l2 = -lse2[bh_idx * g.n_tokens + q_tok];
+    const float dl = delta[bh_idx * g.n_tokens + q_tok];
+    const float c2 = g.scale * kLog2e;
+
+    f32x16 acc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) acc[dt] = zero_tile();
+
+    for (int c = 0; c < pairs; ++c) {
+        // tile c has landed (own loads, then everyone's) and everyone is done
+        // with the other buffer: refill it with tile c + 1
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (c + 1 < pairs) {
+            const uint32_t o = origin_of_pair(c + 1);
+            io.gather(k_rsrc, o, k_lds[(c + 1) & 1]);
+            io.gather(v_rsrc, o, v_lds[(c + 1) & 1]);
+        }
+        const unsigned char* kt_lds = k_lds[c & 1];
+        const unsigned char* vt_lds = v_lds[c & 1];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            f32x16 s = zero_tile(), dp = zero_tile();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    row_frag<D>(kt_lds, 32 * kt, ks, l32, half), qf[ks], s, 0, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    row_frag<D>(vt_lds, 32 * kt, ks, l32, half), dof[ks], dp, 0, 0, 0);
+            f32x16 ds;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, neg_l2));
+                ds[r] = p * (dp[r] - dl);
+            }
+            bf16x8 dsb[2];
+            pack_tile(ds, dsb);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        trans_frag<D>(kt_lds, 32 * kt + 16 * h, dt, lane), dsb[h], acc[dt], 0, 0,
+                        0);
+        }
+    }
+
+    uint16_t* row_ptr = dq + base + q_tok * D;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) store_tile(row_ptr, dt, half, acc[dt], g.scale);
+}
+
+// ---------------------------------------------------------------------------
+// dK / dV
+// ---------------------------------------------------------------------------
+constexpr int PASS_DV = 1, PASS_DK = 2;
+
+template <int D, int NW, int PASS>
+__device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
+                                          const uint16_t* __restrict__ k,
+                                          const uint16_t* __restrict__ v,
+                                          const uint16_t* __restrict__ dout,
+                                          const float* __restrict__ lse2,
+                                          const float* __restrict__ delta,
+                                          const int32_t* __restrict__ sel_idx,
+                                          uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
+                                          const Geom& g, int64_t slices_xcd)
+{
+    constexpr int KS = D / 16, DT = D / 32;
+    constexpr bool DO_DV = (PASS & PASS_DV) != 0, DO_DK = (PASS & PASS_DK) != 0;
+    constexpr int SCAN = 64 * NW;                  // query blocks examined per scan round
+    using IO = TileIO<D, NW>;
+    __shared__ __attribute__((aligned(1024))) unsigned char q_lds[2][IO::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char g_lds[2][IO::TILE_BYTES];
+    __shared__ __attribute__((aligned(256))) float l_lds[2][64];
+    __shared__ __attribute__((aligned(256))) float d_lds[2][64];
+    __shared__ int list_s[SCAN];
+    __shared__ int wave_cnt[NW];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int n = g.n_select, m = g.n_blocks;
+    const int subs = g.block_tokens / 64;
+
+    int j;
+    int64_t bh_idx;
+    {
+        const int64_t w = blockIdx.x;
+        const int64_t per_slice = m;
+        if (w < slices_xcd * per_slice) {
+            const int64_t seq = w >> 3;
+            bh_idx = (seq / per_slice) * 8 + (w & 7);
+            j = (int)(seq % per_slice);
+        } else {
+            bh_idx = w / per_slice;
+            j = (int)(w % per_slice);
+        }
+    }
+    const uint32_t sub_stride = (uint32_t)((64 / g.block_w) * g.grid_w * (D * 2));
+    const int64_t base = bh_idx * g.n_tokens * D;
+    const int32_t* sel_bh = sel_idx + bh_idx * (int64_t)m * n;
+    const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
+    const __amdgpu_buffer_rsrc_t q_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(q + base), 0, slice_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t g_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(dout + base), 0, slice_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t l_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(lse2 + bh_idx * g.n_tokens), 0, (uint32_t)(g.n_tokens * 4), 0x00020000);
+    const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(delta + bh_idx * g.n_tokens), 0, (uint32_t)(g.n_tokens * 4), 0x00020000);
+
+    IO io;
+    io.init(g, lane, wave);
+    auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
+        const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
+        return (uint32_t)((br * g.block_h * g.grid_w + bc * g.block_w) * (D * 2));
+    };
+
+    // this wavefront's 32 key rows: K (and V) as B operands
+    bf16x8 kfb[KS], vfb[DO_DK ? KS : 1];
+    int64_t k_tok;
+    {
+        const int bw_shift = __builtin_ctz((unsigned)g.block_w);
+        const int br = j / g.blocks_per_row, bc = j - br * g.blocks_per_row;
+        const int64_t tok0 = (int64_t)br * g.block_h * g.grid_w + (int64_t)bc * g.block_w;
+        const int t = 32 * wave + l32;
+        const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
+        k_tok = tok0 + (int64_t)rr * g.grid_w + cc;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kfb[ks] = *(const bf16x8*)(k + base + k_tok * D + 16 * ks + 8 * half);
+            if constexpr (DO_DK)
+                vfb[ks] = *(const bf16x8*)(v + base + k_tok * D + 16 * ks + 8 * half);
+        }
+    }
+    const float c2 = g.scale * kLog2e;
+
+    f32x16 acck[DO_DK ? DT : 1], accv[DO_DV ? DT : 1];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        if constexpr (DO_DK) acck[dt] = zero_tile();
+        if constexpr (DO_DV) accv[dt] = zero_tile();
+    }
+
+    // items of a round: (connected query block e, sub-tile ct), e-major
+    auto issue_item = [&](int item, int buf) {
+        const int e = item / subs, ct = item - e * subs;
+        const uint32_t o = origin_of(list_s[e]) + (uint32_t)ct * sub_stride;
+        io.gather(q_rsrc, o, q_lds[buf]);
+        io.gather(g_rsrc, o, g_lds[buf]);
+        if (wave == 0) io.gather_f32(l_rsrc, o / (uint32_t)(D * 2), l_lds[buf]);
+        if (wave == NW - 1) io.gather_f32(d_rsrc, o / (uint32_t)(D * 2), d_lds[buf]);
+    };
+
+    for (int i0 = 0; i0 < m; i0 += SCAN) {
+        // ---- which of the query blocks i0 .. i0+SCAN-1 attend to block j?
+        // ascending order, so the summation order below is fixed
+        const int i_mine = i0 + (int)threadIdx.x;
+        bool hit = false;
+        if (i_mine < m) {
+            hit = i_mine == j;
+            const int32_t* row = sel_bh + (int64_t)i_mine * n;
+            for (int r = 0; r < n; ++r) hit |= row[r] == j;
+        }
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(hit);
+        __syncthreads();                      // previous round's list and tiles fully consumed
+        if (lane == 0) wave_cnt[wave] = __builtin_popcountll(mask);
+        __syncthreads();
+        int offset = 0, total = 0;
+        for (int w = 0; w < NW; ++w) {
+            if (w < wave) offset += wave_cnt[w];
+            total += wave_cnt[w];
+        }
+        if (hit) list_s[offset + __builtin_popcountll(mask & ((1ull << lane) - 1))] = i_mine;
+        __syncthreads();
+
+        const int items = total * subs;
+        if (items > 0) issue_item(0, 0);
+        for (int it = 0; it < items; ++it) {
+            // item `it` has landed and everyone is done with the other buffers
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (it + 1 < items) issue_item(it + 1, (it + 1) & 1);
+            const unsigned char* qt_lds = q_lds[it & 1];
+            const unsigned char* gt_lds = g_lds[it & 1];
+            const float* lt = l_lds[it & 1];
+            const float* dtl = d_lds[it & 1];
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                // S = Q K^T: rows = queries 32 qt .., this lane's column = its key
+                f32x16 s = zero_tile();
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        row_frag<D>(qt_lds, 32 * qt, ks, l32, half), kfb[ks], s, 0, 0, 0);
+                // accumulator element r is query row 8 (r/4) + 4 half + r%4 of the tile
+                f32x16 p;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const float4 l4 = *(const float4*)(lt + 32 * qt + 8 * r4 + 4 * half);
+                    p[4 * r4 + 0] = __builtin_amdgcn_exp2f(fmaf(s[4 * r4 + 0], c2, -l4.x));
+                    p[4 * r4 + 1] = __builtin_amdgcn_exp2f(fmaf(s[4 * r4 + 1], c2, -l4.y));
+                    p[4 * r4 + 2] = __builtin_amdgcn_exp2f(fmaf(s[4 * r4 + 2], c2, -l4.z));
+                    p[4 * r4 + 3] = __builtin_amdgcn_exp2f(fmaf(s[4 * r4 + 3], c2, -l4.w));
+                }
+                if constexpr (DO_DV) {
+                    bf16x8 pb[2];
+                    pack_tile(p, pb);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt)
+                            accv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                trans_frag<D>(gt_lds, 32 * qt + 16 * h, dt, lane), pb[h], accv[dt],
+                                0, 0, 0);
+                }
+                if constexpr (DO_DK) {
+                    f32x16 dp = zero_tile();
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            row_frag<D>(gt_lds, 32 * qt, ks, l32, half), vfb[ks], dp, 0, 0, 0);
+                    f32x16 ds;
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const float4 d4 = *(const float4*)(dtl + 32 * qt + 8 * r4 + 4 * half);
+                        ds[4 * r4 + 0] = p[4 * r4 + 0] * (dp[4 * r4 + 0] - d4.x);
+                        ds[4 * r4 + 1] = p[4 * r4 + 1] * (dp[4 * r4 + 1] - d4.y);
+                        ds[4 * r4 + 2] = p[4 * r4 + 2] * (dp[4 * r4 + 2] - d4.z);
+                        ds[4 * r4 + 3] = p[4 * r4 + 3] * (dp[4 * r4 + 3] - d4.w);
+                    }
+                    bf16x8 dsb[2];
+                    pack_tile(ds, dsb);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt)
+                            acck[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                trans_frag<D>(qt_lds, 32 * qt + 16 * h, dt, lane), dsb[h],
+                                acck[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        if constexpr (DO_DK) store_tile(dk + base + k_tok * D, dt, half, acck[dt], g.scale);
+        if constexpr (DO_DV) store_tile(dv + base + k_tok * D, dt, half, accv[dt], 1.0f);
+    }
+}
+
+}  // namespace bwdm
+
+// delta_l = dO_l . O_l and lse_l * log2(e), one thread per row
+__global__ __launch_bounds__(256) void bwd_mfma_prep_kernel(const uint16_t* __restrict__ out,
+                                                            const uint16_t* __restrict__ dout,
+                                                            const float* __restrict__ lse,
+                                                            float* __restrict__ delta,
+                                                            float* __restrict__ lse2,
+                                                            int64_t rows, int D)
+{
+    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    const uint16_t* o = out + row * D;
+    const uint16_t* gq = dout + row * D;
+    float acc = 0.0f;
+    for (int d = 0; d < D; d += 4) {
+        const float4 a = load4(o + d), b = load4(gq + d);
+        acc = fmaf(a.x, b.x, acc);
+        acc = fmaf(a.y, b.y, acc);
+        acc = fmaf(a.z, b.z, acc);
+        acc = fmaf(a.w, b.w, acc);
+    }
+    delta[row] = acc;
+    lse2[row] = lse[row] * bwdm::kLog2e;
+}
+
+// plain kernels per (head dim, wavefronts per workgroup); the bodies are templates
+#define BSA_BWD_KERNELS(D, NW)                                                                    \
+    __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dq_d##D##_w##NW(                       \
+        const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
+        const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dq, Geom g,      \
+        int64_t slices_xcd)                                                                       \
+    {                                                                                             \
+        bwdm::dq_body<D, NW>(q, k, v, dout, lse2, delta, sel_idx, dq, g, slices_xcd);             \
+    }                                                                                             \
+    __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dv_d##D##_w##NW(                       \
+        const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
+        const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
+        uint16_t* dv, Geom g, int64_t slices_xcd)                                                 \
+    {                                                                                             \
+        bwdm::dkdv_body<D, NW, bwdm::PASS_DV>(q, k, v, dout, lse2, delta, sel_idx, dk, dv, g,     \
+                                              slices_xcd);                                        \
+    }                                                                                             \
+    __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dk_d##D##_w##NW(                       \
+        const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
+        const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
+        uint16_t* dv, Geom g, int64_t slices_xcd)                                                 \
+    {                                                                                             \
+        bwdm::dkdv_body<D, NW, bwdm::PASS_DK>(q, k, v, dout, lse2, delta, sel_idx, dk, dv, g,     \
+                                              slices_xcd);                                        \
+    }
+BSA_BWD_KERNELS(64, 2)
+BSA_BWD_KERNELS(64, 4)
+BSA_BWD_KERNELS(64, 8)
+BSA_BWD_KERNELS(128, 4)
+BSA_BWD_KERNELS(128, 8)
+#undef BSA_BWD_KERNELS
+
+bool bwd_mfma_supported(bool is_bf16, const Geom& g, int D)
+{
+    // a wavefront per 32 rows of a block of 64, 128 or 256 tokens; 64-token
+    // sub-tiles of whole tile rows; 32-bit buffer offsets inside a slice
+    // (head dim 128 with 64-token blocks would leave one wavefront per SIMD)
+    const int b = g.block_tokens;
+    return is_bf16 && (D == 64 || D == 128) && (b == 64 || b == 128 || b == 256) &&
+           !(D == 128 && b == 64) &&
+           64 % g.block_w == 0 && g.n_tokens * D * 2 < ((int64_t)1 << 31);
+}
+
+hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out,
+                           const float* lse, const void* dout, const int32_t* sel_idx, void* dq,
+                           void* dk, void* dv, float* delta, float* lse2, const Geom& g, int D,
+                           int64_t BH, hipStream_t stream)
+{
+    const int64_t rows = BH * g.n_tokens;
+    bwd_mfma_prep_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream>>>(
+        (const uint16_t*)out, (const uint16_t*)dout, lse, delta, lse2, rows, D);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int nw = g.block_tokens / 32;
+    const dim3 grid((unsigned)(BH * g.n_blocks)), block(64 * nw);
+    const int64_t sx = BH - BH % 8;
+#define BSA_LAUNCH(D_, NW_)                                                                       \
+    if (D == D_ && nw == NW_) {                                                                   \
+        bwd_mfma_dq_d##D_##_w##NW_<<<grid, block, 0, stream>>>(                                   \
+            (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
+            lse2, delta, sel_idx, (uint16_t*)dq, g, sx);                                          \
+        if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
+        bwd_mfma_dv_d##D_##_w##NW_<<<grid, block, 0, stream>>>(                                   \
+            (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
+            lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
+        if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
+        bwd_mfma_dk_d##D_##_w##NW_<<<grid, block, 0, stream>>>(                                   \
+            (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
+            lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
+        return hipGetLastError();                                                                 \
+    }
+    BSA_LAUNCH(64, 2)
+    BSA_LAUNCH(64, 4)
+    BSA_LAUNCH(64, 8)
+    BSA_LAUNCH(128, 4)
+    BSA_LAUNCH(128, 8)
+#undef BSA_LAUNCH
+    return hipErrorInvalidValue;
+}
+
+}  // namespace bsa

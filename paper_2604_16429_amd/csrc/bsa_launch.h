@@ -42,4 +42,12 @@ hipError_t launch_bwd(bool is_bf16, const void* q, const void* k, const void* v,
                       void* dk, void* dv, float* delta, const Geom& g, int D, int64_t BH,
                       hipStream_t stream);
 
+// bf16 MFMA backward (head dim 64 or 128, blocks of 64, 128 or 256 tokens);
+// `delta` and `lse2` are fp32 scratch of B*heads*N floats each.
+bool bwd_mfma_supported(bool is_bf16, const Geom& g, int D);
+hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out,
+                           const float* lse, const void* dout, const int32_t* sel_idx, void* dq,
+                           void* dk, void* dv, float* delta, float* lse2, const Geom& g, int D,
+                           int64_t BH, hipStream_t stream);
+
 }  // namespace bsa

@@ -44,7 +44,8 @@ def test_workspace_bytes():
     per = (1 * 2 * m * 32 * 4 + 255) // 256 * 256
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_SELECT) == 2 * per
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_FWD) == 0
-    assert M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD) == 1 * 2 * 2048 * 4
+    # delta and lse * log2(e), fp32 [B, heads, N] each
+    assert M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD) == 2 * (1 * 2 * 2048 * 4)
     assert M.mosaic_bsa_workspace_bytes(good(head_dim=48), binding.OP_SELECT) == 0
 
 

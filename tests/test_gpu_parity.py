@@ -300,6 +300,26 @@ def test_backward_matches_oracle(G, oracle, dtype, H, W, bh, bw, D, n):
     check_grads(cfg, got, ref)
 
 
+@pytest.mark.parametrize("H,W,bh,bw,D,n", [
+    (32, 64, 8, 8, 64, 4),       # 64-token blocks, two wavefronts per block
+    (32, 64, 8, 16, 64, 3),      # 128-token blocks
+    (32, 64, 16, 16, 64, 2),     # 256-token blocks, eight wavefronts per block
+    (16, 128, 4, 32, 128, 0),    # head dim 128, block-diagonal
+    (32, 32, 16, 16, 128, 3),    # head dim 128, 256-token blocks, n = m - 1: dense gradient
+    (24, 64, 8, 16, 128, 5),
+])
+def test_backward_matrix_core_shapes(G, oracle, H, W, bh, bw, D, n):
+    """bf16 shapes that run on the matrix-core backward kernels."""
+    cfg = shape_ns(1, 3, H, W, bh, bw, D, n, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 900 + bh + D))
+    dout = round_to_bf16(rand_qkv(cfg, 901 + bh + D)[0])
+    s = oracle.shape_of(cfg)
+    idx = random_selection(cfg, 41) if n else oracle.select(s, q, k)
+    ref = oracle.bwd(s, q, k, v, dout, idx)
+    got = G.gpu_bwd(cfg, q, k, v, dout, idx)
+    check_grads(cfg, got, ref)
+
+
 def test_backward_gradient_configuration_fields(G, oracle):
     """Seeded smooth fields of the gradient configuration (tile 8x16, D = 128,
     n = 12, dO white) on a reduced grid, arbitrary selection order; reruns are
