@@ -166,7 +166,11 @@ def main():
         },
     }
     if args.with_bwd:
-        dout = up(problem.dout)
+        if problem.dout is not None:
+            dout = up(problem.dout)
+        else:       # workloads without an upstream gradient in their recipe: seeded white noise
+            gen = torch.Generator(device=dev).manual_seed(16429003)
+            dout = torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(q.dtype)
         dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
         ws_b = torch.empty(max(M.mosaic_bsa_workspace_bytes(prm, binding.OP_BWD), 256),
                            dtype=torch.uint8, device=dev)

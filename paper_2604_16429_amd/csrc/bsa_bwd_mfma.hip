@@ -504,28 +504,48 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
 
 }  // namespace bwdm
 
-// delta_l = dO_l . O_l and lse_l * log2(e), one thread per row
+// delta_l = dO_l . O_l and lse_l * log2(e).  A row (D bf16 = 128 or 256 bytes)
+// is read by D/8 adjacent lanes, 16 bytes each, so a wavefront's loads cover
+// whole lines; the partial dot products are summed inside the lane group with
+// DPP steps.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(
+                   __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+template <int D>
 __global__ __launch_bounds__(256) void bwd_mfma_prep_kernel(const uint16_t* __restrict__ out,
                                                             const uint16_t* __restrict__ dout,
                                                             const float* __restrict__ lse,
                                                             float* __restrict__ delta,
                                                             float* __restrict__ lse2,
-                                                            int64_t rows, int D)
+                                                            int64_t rows)
 {
-    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= rows) return;
-    const uint16_t* o = out + row * D;
-    const uint16_t* gq = dout + row * D;
+    constexpr int LPR = D / 8;                      // lanes per row: 8 or 16
+    const int sub = threadIdx.x % LPR;
+    int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPR;
+    const bool valid = row < rows;
+    if (!valid) row = rows - 1;                     // keep the lane group whole for the DPP sums
+    const uint4 a = *(const uint4*)(out + row * D + 8 * sub);
+    const uint4 b = *(const uint4*)(dout + row * D + 8 * sub);
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
     float acc = 0.0f;
-    for (int d = 0; d < D; d += 4) {
-        const float4 a = load4(o + d), b = load4(gq + d);
-        acc = fmaf(a.x, b.x, acc);
-        acc = fmaf(a.y, b.y, acc);
-        acc = fmaf(a.z, b.z, acc);
-        acc = fmaf(a.w, b.w, acc);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        acc = fmaf(__uint_as_float(aw[e] << 16), __uint_as_float(bw[e] << 16), acc);
+        acc = fmaf(__uint_as_float(aw[e] & 0xffff0000u), __uint_as_float(bw[e] & 0xffff0000u),
+                   acc);
     }
-    delta[row] = acc;
-    lse2[row] = lse[row] * bwdm::kLog2e;
+    acc = dpp_add<0xB1>(acc);                       // quad_perm [1,0,3,2]
+    acc = dpp_add<0x4E>(acc);                       // quad_perm [2,3,0,1]
+    acc = dpp_add<0x141>(acc);                      // row_half_mirror: 8 lanes
+    if (LPR == 16) acc = dpp_add<0x140>(acc);       // row_mirror: 16 lanes
+    if (valid && sub == 0) {
+        delta[row] = acc;
+        lse2[row] = lse[row] * bwdm::kLog2e;
+    }
 }
 
 // plain kernels per (head dim, wavefronts per workgroup); the bodies are templates
@@ -577,8 +597,16 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
                            int64_t BH, hipStream_t stream)
 {
     const int64_t rows = BH * g.n_tokens;
-    bwd_mfma_prep_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream>>>(
-        (const uint16_t*)out, (const uint16_t*)dout, lse, delta, lse2, rows, D);
+    {
+        const int64_t threads = rows * (D / 8);
+        const dim3 pgrid((unsigned)((threads + 255) / 256));
+        if (D == 64)
+            bwd_mfma_prep_kernel<64><<<pgrid, dim3(256), 0, stream>>>(
+                (const uint16_t*)out, (const uint16_t*)dout, lse, delta, lse2, rows);
+        else
+            bwd_mfma_prep_kernel<128><<<pgrid, dim3(256), 0, stream>>>(
+                (const uint16_t*)out, (const uint16_t*)dout, lse, delta, lse2, rows);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int nw = g.block_tokens / 32;
