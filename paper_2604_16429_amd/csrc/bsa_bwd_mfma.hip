@@ -576,6 +576,20 @@ __global__ __launch_bounds__(256) void bwd_mfma_prep_kernel(const uint16_t* __re
 BSA_BWD_KERNELS(64, 2)
 BSA_BWD_KERNELS(64, 4)
 BSA_BWD_KERNELS(64, 8)
+// head dim 64: both accumulators fit, dK and dV in one pass
+#define BSA_BWD_FUSED(NW)                                                                         \
+    __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dkdv_d64_w##NW(                        \
+        const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
+        const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
+        uint16_t* dv, Geom g, int64_t slices_xcd)                                                 \
+    {                                                                                             \
+        bwdm::dkdv_body<64, NW, bwdm::PASS_DV | bwdm::PASS_DK>(q, k, v, dout, lse2, delta,        \
+                                                               sel_idx, dk, dv, g, slices_xcd);   \
+    }
+BSA_BWD_FUSED(2)
+BSA_BWD_FUSED(4)
+BSA_BWD_FUSED(8)
+#undef BSA_BWD_FUSED
 BSA_BWD_KERNELS(128, 4)
 BSA_BWD_KERNELS(128, 8)
 #undef BSA_BWD_KERNELS
@@ -627,9 +641,21 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
             lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
         return hipGetLastError();                                                                 \
     }
-    BSA_LAUNCH(64, 2)
-    BSA_LAUNCH(64, 4)
-    BSA_LAUNCH(64, 8)
+#define BSA_LAUNCH_FUSED(NW_)                                                                     \
+    if (D == 64 && nw == NW_) {                                                                   \
+        bwd_mfma_dq_d64_w##NW_<<<grid, block, 0, stream>>>(                                       \
+            (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
+            lse2, delta, sel_idx, (uint16_t*)dq, g, sx);                                          \
+        if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
+        bwd_mfma_dkdv_d64_w##NW_<<<grid, block, 0, stream>>>(                                     \
+            (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
+            lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
+        return hipGetLastError();                                                                 \
+    }
+    BSA_LAUNCH_FUSED(2)
+    BSA_LAUNCH_FUSED(4)
+    BSA_LAUNCH_FUSED(8)
+#undef BSA_LAUNCH_FUSED
     BSA_LAUNCH(128, 4)
     BSA_LAUNCH(128, 8)
 #undef BSA_LAUNCH
