@@ -70,16 +70,13 @@ struct TileIO {
     __device__ __forceinline__ void init(const Geom& g, int lane, int wave_)
     {
         wave = wave_;
-        const int bw_shift = __builtin_ctz((unsigned)g.block_w);
 #pragma unroll
         for (int j = 0; j < MINE; ++j) {
             const int slab = wave + j * NW;
             const int t = RPS * slab + lane / LPR;                    // token row 0..63
-            const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
-            voff[j] = (uint32_t)((rr * g.grid_w + cc) * ROW_BYTES + swz(t, lane % LPR) * 16);
+            voff[j] = (uint32_t)(sub_tile_pos(g, t) * ROW_BYTES + swz(t, lane % LPR) * 16);
         }
-        const int rr = lane >> bw_shift, cc = lane & (g.block_w - 1);
-        tok_off = (uint32_t)((rr * g.grid_w + cc) * 4);
+        tok_off = (uint32_t)(sub_tile_pos(g, lane) * 4);
     }
     // this wavefront's share of one tile (origin: byte offset of the sub-tile's
     // first token in a [N, D] bf16 slice)
@@ -206,7 +203,6 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
             i = (int)(w % per_slice);
         }
     }
-    const uint32_t sub_stride = (uint32_t)((64 / g.block_w) * g.grid_w * (D * 2));
     const int64_t base = bh_idx * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
@@ -224,7 +220,7 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
     const int pairs = (n + 1) * subs;
     auto origin_of_pair = [&](int c) -> uint32_t {   // attended block c / subs, sub-tile c % subs
         const int cb = c / subs, ct = c - cb * subs;
-        return origin_of(cb == 0 ? i : sel_row[cb - 1]) + (uint32_t)ct * sub_stride;
+        return origin_of(cb == 0 ? i : sel_row[cb - 1]) + (uint32_t)(sub_tile_first(g, ct) * (D * 2));
     };
 
     io.gather(k_rsrc, origin_of_pair(0), k_lds[0]);
@@ -348,7 +344,6 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
             j = (int)(w % per_slice);
         }
     }
-    const uint32_t sub_stride = (uint32_t)((64 / g.block_w) * g.grid_w * (D * 2));
     const int64_t base = bh_idx * g.n_tokens * D;
     const int32_t* sel_bh = sel_idx + bh_idx * (int64_t)m * n;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
@@ -397,7 +392,7 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
     // items of a round: (connected query block e, sub-tile ct), e-major
     auto issue_item = [&](int item, int buf) {
         const int e = item / subs, ct = item - e * subs;
-        const uint32_t o = origin_of(list_s[e]) + (uint32_t)ct * sub_stride;
+        const uint32_t o = origin_of(list_s[e]) + (uint32_t)(sub_tile_first(g, ct) * (D * 2));
         io.gather(q_rsrc, o, q_lds[buf]);
         io.gather(g_rsrc, o, g_lds[buf]);
         if (wave == 0) io.gather_f32(l_rsrc, o / (uint32_t)(D * 2), l_lds[buf]);
@@ -597,12 +592,13 @@ BSA_BWD_KERNELS(128, 8)
 bool bwd_mfma_supported(bool is_bf16, const Geom& g, int D)
 {
     // a wavefront per 32 rows of a block of 64, 128 or 256 tokens; 64-token
-    // sub-tiles of whole tile rows; 32-bit buffer offsets inside a slice
+    // sub-tiles (tile width a power of two: whole tile rows, or 64-token runs of
+    // one row); 32-bit buffer offsets inside a slice
     // (head dim 128 with 64-token blocks would leave one wavefront per SIMD)
     const int b = g.block_tokens;
     return is_bf16 && (D == 64 || D == 128) && (b == 64 || b == 128 || b == 256) &&
            !(D == 128 && b == 64) &&
-           64 % g.block_w == 0 && g.n_tokens * D * 2 < ((int64_t)1 << 31);
+           (g.block_w & (g.block_w - 1)) == 0 && g.n_tokens * D * 2 < ((int64_t)1 << 31);
 }
 
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out,

@@ -31,6 +31,23 @@ __device__ __forceinline__ int64_t token_of(const Geom& g, int beta, int tau)
     return (int64_t)(br * g.block_h + rr) * g.grid_w + (bc * g.block_w + cc);
 }
 
+// 64-token sub-tiles of a block whose width is a power of two: sub-tile ct holds
+// the in-tile positions 64 ct .. 64 ct + 63, i.e. whole tile rows when the width
+// divides 64 and a 64-token run of one tile row when 64 divides the width (a
+// block-contiguous layout is the case of tiles one row high).
+// Offset, in tokens, of the sub-tile's first token from the block's first token:
+__device__ __forceinline__ int sub_tile_first(const Geom& g, int ct)
+{
+    const int t0 = 64 * ct;
+    return (t0 >> __builtin_ctz((unsigned)g.block_w)) * g.grid_w + (t0 & (g.block_w - 1));
+}
+// Offset, in tokens, of position u (0..63) of a sub-tile from its first token:
+__device__ __forceinline__ int sub_tile_pos(const Geom& g, int u)
+{
+    const int w = g.block_w < 64 ? g.block_w : 64;
+    return (u >> __builtin_ctz((unsigned)w)) * g.grid_w + (u & (w - 1));
+}
+
 // bf16 <-> fp32 on raw bit patterns
 __device__ __forceinline__ float bf16_to_f32(uint16_t b)
 {

@@ -1,6 +1,6 @@
 // Block-sparse attention forward on the gfx950 matrix cores (bf16 MFMA, fp32
 // online softmax).  Specialised for head dim 64 and tiles of 64*T tokens whose
-// width divides 64; a tile is processed as T sub-blocks of 64 queries (one
+// width is a power of two; a tile is processed as T sub-blocks of 64 queries (one
 // wavefront each) against T sub-tiles of 64 keys per attended block.
 //
 // Every token of query block i attends, in one softmax, to the tokens of block
@@ -248,9 +248,6 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
         i = (int)(item / groups);
         qsub = (int)(item - (int64_t)i * groups) * NW + wave;
     }
-    // byte distance between consecutive 64-token sub-tiles of a block: 64/bw
-    // grid rows (the tile width divides 64)
-    const uint32_t sub_stride = (uint32_t)((64 / g.block_w) * g.grid_w * (D * 2));
     const int64_t base = bh_idx * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     q += base; out += base;
@@ -278,16 +275,15 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
         return sel_row[c - 1];
     };
 
-    // the tile width divides 64, so it is a power of two
+    // the tile width is a power of two
     const int bw_shift = __builtin_ctz((unsigned)g.block_w);
-    // byte offset (inside a block) of the 16-byte chunk this lane gathers in
-    // slab r: tile row 8r + lane/8, global chunk = swizzle of its LDS slot
+    // byte offset (inside a 64-token sub-tile) of the 16-byte chunk this lane
+    // gathers in slab r: sub-tile row 8r + lane/8, global chunk = swizzle of its LDS slot
     uint32_t voff[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const int t = 8 * r + (lane >> 3);
-        const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
-        voff[r] = (uint32_t)(((rr * g.grid_w + cc) * D + swz(t, lane & 7) * 8) * 2);
+        voff[r] = (uint32_t)((sub_tile_pos(g, t) * D + swz(t, lane & 7) * 8) * 2);
     }
     auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
         const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
@@ -400,7 +396,7 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     int pcb = 0, pct = 0;
     auto next_origin = [&]() -> uint32_t {
         if (++pct == subs) { pct = 0; ++pcb; }
-        return origin_of(block_at(pcb <= n ? pcb : n)) + (uint32_t)pct * sub_stride;
+        return origin_of(block_at(pcb <= n ? pcb : n)) + (uint32_t)(sub_tile_first(g, pct) * (D * 2));
     };
     uint32_t o1 = next_origin();                       // origin of pair c + 1
 
@@ -555,11 +551,12 @@ BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg4_kernel, 4)
 
 bool fwd_mfma_supported(bool is_bf16, const Geom& g, int D)
 {
-    // tiles of 64*T tokens whose width divides 64: every 64-token sub-tile is
-    // then a whole number of tile rows, a fixed byte distance apart
+    // tiles of 64*T tokens whose width is a power of two: every 64-token
+    // sub-tile is then whole tile rows or a 64-token run of one tile row
     // (a token row is 128 bytes, so 16-byte chunks never straddle tokens);
     // buffer offsets inside a slice are 32-bit
-    return is_bf16 && D == 64 && g.block_tokens % 64 == 0 && 64 % g.block_w == 0 &&
+    return is_bf16 && D == 64 && g.block_tokens % 64 == 0 &&
+           (g.block_w & (g.block_w - 1)) == 0 &&
            g.n_tokens * D * 2 < ((int64_t)1 << 31);
 }
 

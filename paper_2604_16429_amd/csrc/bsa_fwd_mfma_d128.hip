@@ -104,7 +104,6 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
             i = (int)(w % per_slice);
         }
     }
-    const uint32_t sub_stride = (uint32_t)((64 / g.block_w) * g.grid_w * ROW_BYTES);
     const int64_t base = bh_idx * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     q += base; out += base;
@@ -143,9 +142,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         voff_par[par] = (uint32_t)((lane >> 4) * ROW_BYTES + swz(row, lane & 15) * 16);
     }
     auto slab_offset = [&](int hh, int slab) -> uint32_t {   // first token of a slab, bytes
-        const int t0 = 32 * hh + 4 * slab;
-        const int rr = t0 >> bw_shift, cc = t0 & (g.block_w - 1);
-        return (uint32_t)((rr * g.grid_w + cc) * ROW_BYTES);
+        return (uint32_t)(sub_tile_pos(g, 32 * hh + 4 * slab) * ROW_BYTES);
     };
     auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
         const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
@@ -244,7 +241,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     int pcb = 0, pct = 0;
     auto next_origin = [&]() -> uint32_t {
         if (++pct == subs) { pct = 0; ++pcb; }
-        return origin_of(block_at(pcb <= n ? pcb : n)) + (uint32_t)pct * sub_stride;
+        return origin_of(block_at(pcb <= n ? pcb : n)) + (uint32_t)(sub_tile_first(g, pct) * ROW_BYTES);
     };
     uint32_t o0 = origin_of(i);                        // origin of pair c
     uint32_t o1 = next_origin();                       // origin of pair c + 1
@@ -471,10 +468,11 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
 bool fwd_mfma_d128_supported(bool is_bf16, const Geom& g, int D)
 {
     // query block = 4 wavefronts x 32 rows; 64-key sub-tiles of whole tile rows
-    // (the tile width divides 64) whose 4-token load slabs are contiguous (the
+    // or 64-token runs of a row (the tile width is a power of two) whose 4-token
+    // load slabs are contiguous (the
     // width is at least 4); buffer offsets inside a slice are 32-bit
-    return is_bf16 && D == 128 && g.block_tokens == 32 * NW && 64 % g.block_w == 0 &&
-           g.block_w >= 4 && g.n_tokens * D * 2 < ((int64_t)1 << 31);
+    return is_bf16 && D == 128 && g.block_tokens == 32 * NW &&
+           (g.block_w & (g.block_w - 1)) == 0 && g.block_w >= 4 && g.n_tokens * D * 2 < ((int64_t)1 << 31);
 }
 
 hipError_t launch_fwd_mfma_d128(const void* q, const void* k, const void* v,

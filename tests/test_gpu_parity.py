@@ -88,6 +88,9 @@ def test_edge_shapes(G, oracle, dtype, H, W, bh, bw, D, n):
     (32, 64, 4, 32, 3),      # 128-token tiles, wide
     (32, 64, 16, 4, 6),      # 64-token tiles, narrow
     (48, 64, 24, 8, 2),      # 192-token tiles: three sub-blocks
+    (24, 128, 1, 64, 4),     # block-contiguous layout: a block is 64 consecutive tokens
+    (12, 256, 1, 128, 3),    # block-contiguous, 128-token blocks
+    (8, 256, 2, 128, 2),     # two rows of 128: sub-tiles are halves of a tile row
 ])
 def test_mfma_tile_shapes(G, oracle, H, W, bh, bw, n):
     """bf16, D = 64 tiles of 64*T tokens (matrix-core forward kernel)."""
@@ -103,6 +106,7 @@ def test_mfma_tile_shapes(G, oracle, H, W, bh, bw, n):
     (16, 128, 2, 64, 3),
     (64, 32, 32, 4, 5),      # 4-token load slabs, the narrowest supported tile
     (8, 64, 8, 16, 1),       # one row of tiles
+    (16, 256, 1, 128, 4),    # block-contiguous layout: a block is 128 consecutive tokens
 ])
 def test_mfma_d128_tile_shapes(G, oracle, H, W, bh, bw, n):
     """bf16, D = 128, tiles of 128 tokens (four-wavefront matrix-core kernel)."""
@@ -307,6 +311,8 @@ def test_backward_matches_oracle(G, oracle, dtype, H, W, bh, bw, D, n):
     (16, 128, 4, 32, 128, 0),    # head dim 128, block-diagonal
     (32, 32, 16, 16, 128, 3),    # head dim 128, 256-token blocks, n = m - 1: dense gradient
     (24, 64, 8, 16, 128, 5),
+    (16, 128, 1, 128, 128, 3),   # block-contiguous layout, 128-token blocks
+    (8, 256, 1, 256, 64, 2),     # block-contiguous layout, 256-token blocks
 ])
 def test_backward_matrix_core_shapes(G, oracle, H, W, bh, bw, D, n):
     """bf16 shapes that run on the matrix-core backward kernels."""
