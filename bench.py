@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3, help="configuration id (1-5)")
+    ap.add_argument("--config", type=int, default=3, help="configuration id (1-5: the benchmark configurations; 6, 7: the paper's stage-1 shape, block-contiguous and tiled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-bwd", action="store_true",
                     help="also run the backward (selection held fixed) after the timed steps "

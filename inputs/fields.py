@@ -84,6 +84,14 @@ CONFIGS = {
     4: GridConfig(4, 1, 16, 720, 1440, 16, 16, 64, 16, "bf16", 24.0, 0.1),
     5: GridConfig(5, 4, 16, 120, 240, 8, 16, 128, 12, "bf16", 6.0, 0.1,
                   with_dout=True),
+    # Shapes of the paper's first stage (49,152 tokens, sparse block size 128,
+    # 24 selected blocks; architecture table), which the five benchmark
+    # configurations do not cover.  6: block-contiguous layout, a block is 128
+    # consecutive tokens (what a nested HEALPix ordering gives): 384 tiles one
+    # row high.  7: the same token count as 8 x 16 tiles of a 192 x 256 grid,
+    # to measure what gathering 2-D tiles costs against contiguous blocks.
+    6: GridConfig(6, 8, 16, 384, 128, 1, 128, 64, 24, "bf16", 6.0, 0.1),
+    7: GridConfig(7, 8, 16, 192, 256, 8, 16, 64, 24, "bf16", 6.0, 0.1),
 }
 
 

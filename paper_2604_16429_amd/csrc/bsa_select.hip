@@ -20,60 +20,59 @@ namespace bsa {
 // ---------------------------------------------------------------------------
 // pooling
 // ---------------------------------------------------------------------------
-// One workgroup per (tensor, batch*head, row of tiles).  A work item is (tile
-// in that row, group of VEC channels); it walks the tile's tokens in in-tile
-// row-major order, which is the pinned summation order.  Consecutive lanes
-// take consecutive channel groups, so every load covers whole 128-byte lines
-// and each tile row (bw*D elements, contiguous in memory) is consumed by
-// consecutive iterations.
+// A work item is (tile, group of VEC channels); it walks the tile's tokens in
+// in-tile row-major order, which is the pinned summation order.  The items of
+// one (tensor, batch*head) are numbered tile-major and dealt to workgroups of
+// 256 in order: consecutive lanes take consecutive channel groups, so every
+// load covers whole 128-byte lines and the tiles of a tile row (bw*D elements
+// each, contiguous in memory) are consumed side by side.
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
                                                    const T* __restrict__ k,
                                                    float* __restrict__ qbar,
                                                    float* __restrict__ kbar, Geom g, int D,
-                                                   int64_t BH)
+                                                   int64_t BH, int wgs_per_slice)
 {
-    // blockIdx.x = (tensor * BH + batch*head) * tile_rows + tile_row
-    const int tile_rows = g.n_blocks / g.blocks_per_row;
-    const int tile_row = blockIdx.x % tile_rows;
-    int64_t bh_idx = blockIdx.x / tile_rows;     // tensor * BH + batch*head
+    // blockIdx.x = (tensor * BH + batch*head) * wgs_per_slice + chunk of 256 items
+    const int chunk = blockIdx.x % wgs_per_slice;
+    int64_t bh_idx = blockIdx.x / wgs_per_slice;     // tensor * BH + batch*head
     const bool is_k = bh_idx >= BH;
     if (is_k) bh_idx -= BH;
     const T* __restrict__ x = is_k ? k : q;
     float* __restrict__ xbar = is_k ? kbar : qbar;
     const int groups = D / VEC;
-    const int items = g.blocks_per_row * groups;
+    const int items = g.n_blocks * groups;
     const float inv_b = 1.0f / (float)g.block_tokens;
     x += bh_idx * g.n_tokens * D;
 
-    for (int item = threadIdx.x; item < items; item += blockDim.x) {
-        const int tile_col = item / groups;
-        const int ch = (item - tile_col * groups) * VEC;
-        float acc[VEC];
+    const int item = chunk * 256 + (int)threadIdx.x;
+    if (item >= items) return;
+    const int beta = item / groups;
+    const int ch = (item - beta * groups) * VEC;
+    const int tile_row = beta / g.blocks_per_row, tile_col = beta - tile_row * g.blocks_per_row;
+    float acc[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
-        for (int rr = 0; rr < g.block_h; ++rr) {
-            const T* row = x + ((int64_t)(tile_row * g.block_h + rr) * g.grid_w +
-                                (int64_t)tile_col * g.block_w) * D + ch;
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+    for (int rr = 0; rr < g.block_h; ++rr) {
+        const T* row = x + ((int64_t)(tile_row * g.block_h + rr) * g.grid_w +
+                            (int64_t)tile_col * g.block_w) * D + ch;
 #pragma unroll 8
-            for (int cc = 0; cc < g.block_w; ++cc) {
+        for (int cc = 0; cc < g.block_w; ++cc) {
 #pragma unroll
-                for (int e4 = 0; e4 < VEC; e4 += 4) {
-                    const float4 v = load4(row + (int64_t)cc * D + e4);
-                    acc[e4 + 0] = acc[e4 + 0] + v.x;
-                    acc[e4 + 1] = acc[e4 + 1] + v.y;
-                    acc[e4 + 2] = acc[e4 + 2] + v.z;
-                    acc[e4 + 3] = acc[e4 + 3] + v.w;
-                }
+            for (int e4 = 0; e4 < VEC; e4 += 4) {
+                const float4 v = load4(row + (int64_t)cc * D + e4);
+                acc[e4 + 0] = acc[e4 + 0] + v.x;
+                acc[e4 + 1] = acc[e4 + 1] + v.y;
+                acc[e4 + 2] = acc[e4 + 2] + v.z;
+                acc[e4 + 3] = acc[e4 + 3] + v.w;
             }
         }
-        const int beta = tile_row * g.blocks_per_row + tile_col;
-        float* dst = xbar + (bh_idx * g.n_blocks + beta) * D + ch;
-#pragma unroll
-        for (int e4 = 0; e4 < VEC; e4 += 4)
-            store4(dst + e4, make_float4(acc[e4] * inv_b, acc[e4 + 1] * inv_b,
-                                         acc[e4 + 2] * inv_b, acc[e4 + 3] * inv_b));
     }
+    float* dst = xbar + (bh_idx * g.n_blocks + beta) * D + ch;
+#pragma unroll
+    for (int e4 = 0; e4 < VEC; e4 += 4)
+        store4(dst + e4, make_float4(acc[e4] * inv_b, acc[e4 + 1] * inv_b,
+                                     acc[e4 + 2] * inv_b, acc[e4 + 3] * inv_b));
 }
 
 // ---------------------------------------------------------------------------
@@ -265,12 +264,11 @@ template <typename T, int VEC>
 static hipError_t launch_pool_t(const void* q, const void* k, float* qbar, float* kbar,
                                 const Geom& g, int D, int64_t BH, hipStream_t stream)
 {
-    const int tile_rows = g.n_blocks / g.blocks_per_row;
-    const int items = g.blocks_per_row * (D / VEC);
-    const int threads = items >= 256 ? 256 : ((items + 63) / 64) * 64;
-    dim3 grid((unsigned)(2 * BH * tile_rows));
-    hipLaunchKernelGGL((pool_kernel<T, VEC>), grid, dim3(threads), 0, stream, (const T*)q,
-                       (const T*)k, qbar, kbar, g, D, BH);
+    const int items = g.n_blocks * (D / VEC);
+    const int wgs_per_slice = (items + 255) / 256;
+    dim3 grid((unsigned)(2 * BH * wgs_per_slice));
+    hipLaunchKernelGGL((pool_kernel<T, VEC>), grid, dim3(256), 0, stream, (const T*)q,
+                       (const T*)k, qbar, kbar, g, D, BH, wgs_per_slice);
     return hipGetLastError();
 }
 
