@@ -228,3 +228,46 @@ def bwd(s, q, k, v, dout, sel_idx, scale: float = 0.0):
                        dk.ctypes.data_as(ctypes.c_void_p),
                        dv.ctypes.data_as(ctypes.c_void_p))
     return dq, dk, dv
+
+
+# ---------------------------------------------------------------------------
+# Grouped query attention (the paper's Attention paragraph: the queries attend
+# to a smaller number of shared key-value heads).  Reading taken here: query
+# head a reads key/value head a // (heads / kv_heads); pooling, scoring and
+# selection stay per query head, on the key head that the query head reads.
+# Written out as the definition: give every query head its own copy of the
+# key/value head it reads and run the one-head-each path; the gradient of a
+# shared head is the sum of the gradients of its copies.
+# ---------------------------------------------------------------------------
+def expand_kv(x, heads: int):
+    """[B, kv_heads, N, D] -> [B, heads, N, D], head a <- x[:, a // group]."""
+    kv_heads = x.shape[1]
+    if heads % kv_heads:
+        raise ValueError("kv_heads must divide heads")
+    return np.repeat(np.asarray(x), heads // kv_heads, axis=1)
+
+
+def reduce_kv(dx, kv_heads: int):
+    """[B, heads, N, D] -> [B, kv_heads, N, D]: sum over each group, in
+    ascending head order."""
+    B, h, N, D = dx.shape
+    group = h // kv_heads
+    out = np.zeros((B, kv_heads, N, D), dtype=dx.dtype)
+    for a in range(h):
+        out[:, a // group] += dx[:, a]
+    return out
+
+
+def select_gqa(s, q, k):
+    return select(s, q, expand_kv(k, s.heads))
+
+
+def fwd_gqa(s, q, k, v, sel_idx, scale: float = 0.0):
+    return fwd(s, q, expand_kv(k, s.heads), expand_kv(v, s.heads), sel_idx, scale)
+
+
+def bwd_gqa(s, q, k, v, dout, sel_idx, scale: float = 0.0):
+    kv_heads = k.shape[1]
+    dq, dk, dv = bwd(s, q, expand_kv(k, s.heads), expand_kv(v, s.heads), dout,
+                     sel_idx, scale)
+    return dq, reduce_kv(dk, kv_heads), reduce_kv(dv, kv_heads)

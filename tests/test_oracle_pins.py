@@ -390,3 +390,80 @@ def test_softmax_jacobian_rows_vanish(oracle):
     ones = np.ones_like(dout)
     _, _, dv1 = oracle.bwd(s, q, k, v, ones, idx)
     np.testing.assert_allclose(dv1.sum(axis=2), c.n_tokens, rtol=0, atol=1e-10)
+
+
+# --------------------------------------------------------------------------
+# grouped query attention (Attention paragraph: shared key-value heads)
+# --------------------------------------------------------------------------
+def _kv(c, seed, kv_heads):
+    """Key/value tensors [B, kv_heads, N, D]."""
+    rng = np.random.default_rng(seed)
+    shp = (c.batch, kv_heads, c.n_tokens, c.head_dim)
+    return tuple(rng.standard_normal(shp).astype(np.float32) for _ in range(2))
+
+
+def test_gqa_all_blocks_selected_is_library_grouped_attention(oracle):
+    """n = m - 1: the result is dense attention, which the library computes
+    with its own grouped-head convention (query head a reads head a // group)."""
+    c = shape_ns(2, 6, 8, 8, 4, 4, 16, 3)       # m = 4, 6 query heads on 2 kv heads
+    s = oracle.shape_of(c)
+    q = rand_qkv(c, 40)[0]
+    k, v = _kv(c, 41, 2)
+    idx = oracle.select_gqa(s, q, k)
+    out, _ = oracle.fwd_gqa(s, q, k, v, idx)
+    tq, tk, tv = (torch.from_numpy(x).double() for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, enable_gqa=True)
+    np.testing.assert_allclose(out, ref.numpy(), rtol=0, atol=1e-12)
+    # gradients of sum(O * dO) against the library's autograd
+    dout = rand_qkv(c, 42)[0]
+    dq, dk, dv = oracle.bwd_gqa(s, q, k, v, dout, idx)
+    tq, tk, tv = (t.requires_grad_() for t in (tq, tk, tv))
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, enable_gqa=True)
+    (o * torch.from_numpy(dout).double()).sum().backward()
+    assert dk.shape == k.shape and dv.shape == v.shape
+    np.testing.assert_allclose(dq, tq.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dk, tk.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=0, atol=1e-12)
+
+
+def test_gqa_head_by_head_equals_single_head_problems(oracle):
+    """Sparse case: query head a of the grouped problem is the one-head
+    problem on (q[:, a], k[:, a // group], v[:, a // group]), picked out here by
+    indexing; the gradient of a shared head is the sum over its query heads."""
+    c = shape_ns(1, 4, 12, 16, 4, 4, 8, 3)      # m = 12
+    s = oracle.shape_of(c)
+    q = rand_qkv(c, 43)[0]
+    k, v = _kv(c, 44, 2)
+    dout = rand_qkv(c, 45)[0]
+    idx = oracle.select_gqa(s, q, k)
+    out, lse = oracle.fwd_gqa(s, q, k, v, idx)
+    dq, dk, dv = oracle.bwd_gqa(s, q, k, v, dout, idx)
+    c1 = shape_ns(1, 1, 12, 16, 4, 4, 8, 3)
+    s1 = oracle.shape_of(c1)
+    dk_sum, dv_sum = np.zeros_like(dk), np.zeros_like(dv)
+    for a in range(4):
+        u = a // 2
+        q1, k1, v1, d1 = q[:, a:a + 1], k[:, u:u + 1], v[:, u:u + 1], dout[:, a:a + 1]
+        idx1 = oracle.select(s1, q1, k1)
+        assert np.array_equal(idx1, idx[:, a:a + 1])
+        o1, l1 = oracle.fwd(s1, q1, k1, v1, idx1)
+        np.testing.assert_array_equal(o1, out[:, a:a + 1])
+        np.testing.assert_array_equal(l1, lse[:, a:a + 1])
+        g = oracle.bwd(s1, q1, k1, v1, d1, idx1)
+        np.testing.assert_array_equal(g[0], dq[:, a:a + 1])
+        dk_sum[:, u:u + 1] += g[1]
+        dv_sum[:, u:u + 1] += g[2]
+    np.testing.assert_allclose(dk, dk_sum, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dv, dv_sum, rtol=0, atol=1e-13)
+    # the two query heads of a group see the same keys but select differently
+    assert not np.array_equal(idx[:, 0], idx[:, 1])
+
+
+def test_gqa_with_one_head_per_group_is_the_plain_path(oracle):
+    c = shape_ns(1, 3, 8, 8, 4, 4, 8, 2)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 46)
+    idx = oracle.select(s, q, k)
+    assert np.array_equal(oracle.select_gqa(s, q, k), idx)
+    np.testing.assert_array_equal(oracle.fwd_gqa(s, q, k, v, idx)[0],
+                                  oracle.fwd(s, q, k, v, idx)[0])
