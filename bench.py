@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3, help="configuration id (1-5: the benchmark configurations; 6, 7: the paper's stage-1 shape, block-contiguous and tiled)")
+    ap.add_argument("--config", type=int, default=3, help="configuration id (1-5: the benchmark configurations; 6, 7: the paper's stage-1 shape, block-contiguous and tiled; 8, 9: configurations 3 and 6 with 4 query heads per key/value head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-bwd", action="store_true",
                     help="also run the backward (selection held fixed) after the timed steps "
@@ -59,9 +59,9 @@ def cpu_baseline(problem, cfg):
     s = bsa_oracle.shape_of(sub)
     q, k, v = problem.q[:nb], problem.k[:nb], problem.v[:nb]
     t0 = time.perf_counter()
-    idx = bsa_oracle.select(s, q, k)
+    idx = bsa_oracle.select_gqa(s, q, k)
     t1 = time.perf_counter()
-    bsa_oracle.fwd(s, q, k, v, idx)
+    bsa_oracle.fwd_gqa(s, q, k, v, idx)
     t2 = time.perf_counter()
     return {
         "value": nb * cfg.n_tokens / (t2 - t0), "unit": "tokens/s",
@@ -98,7 +98,8 @@ def main():
 
     q, k, v = up(problem.q), up(problem.k), up(problem.v)
     prm = M.Params(cfg.batch, cfg.heads, cfg.grid_h, cfg.grid_w, cfg.block_h, cfg.block_w,
-                   cfg.head_dim, cfg.n_select, binding.BF16 if is_bf16 else binding.F32, 0.0)
+                   cfg.head_dim, cfg.n_select, binding.BF16 if is_bf16 else binding.F32, 0.0,
+                   cfg.kv_heads)
     idx = torch.empty((cfg.batch, cfg.heads, cfg.n_blocks, cfg.n_select), dtype=torch.int32,
                       device=dev)
     out = torch.empty_like(q)
@@ -134,7 +135,8 @@ def main():
     flops = cfg.fwd_flops()
     eff_tflops = flops / (fwd_ms * 1e-3) / 1e12
     esz = 2 if is_bf16 else 4
-    compulsory = 4 * cfg.batch * cfg.heads * cfg.n_tokens * cfg.head_dim * esz
+    kv_heads = cfg.kv_heads or cfg.heads
+    compulsory = 2 * cfg.batch * (cfg.heads + kv_heads) * cfg.n_tokens * cfg.head_dim * esz
     traffic = MEASURED_FWD_TRAFFIC_BYTES.get(args.config)
 
     result = {
@@ -150,7 +152,8 @@ def main():
             "workload": (f"config {cfg.config_id}: {cfg.grid_h}x{cfg.grid_w} lat-lon grid "
                          f"({cfg.n_tokens} tokens), batch {cfg.batch}, {cfg.heads} heads, "
                          f"head_dim {cfg.head_dim}, tiles {cfg.block_h}x{cfg.block_w}, "
-                         f"local + top-{cfg.n_select} blocks"),
+                         f"local + top-{cfg.n_select} blocks"
+                         + (f", {cfg.kv_heads} key/value heads" if cfg.kv_heads else "")),
             "tokens_per_step": tokens,
         },
         "select_ms": sel_ms, "fwd_ms": fwd_ms,
@@ -171,7 +174,7 @@ def main():
         else:       # workloads without an upstream gradient in their recipe: seeded white noise
             gen = torch.Generator(device=dev).manual_seed(16429003)
             dout = torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(q.dtype)
-        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         ws_b = torch.empty(max(M.mosaic_bsa_workspace_bytes(prm, binding.OP_BWD), 256),
                            dtype=torch.uint8, device=dev)
         reps = max(2, args.steps // 4)

@@ -29,9 +29,11 @@
  *             device memory and never synchronises.  All work is enqueued on
  *             `hip_stream` (a hipStream_t passed as void*, NULL = default
  *             stream); buffers must stay valid until that work has finished.
- *   Layout    q, k, v, out, dout, dq, dk, dv: [batch, heads, N, head_dim]
- *             contiguous, head_dim fastest, element type given by
- *             params->dtype, base pointers 16-byte aligned.
+ *   Layout    q, out, dout, dq: [batch, heads, N, head_dim]; k, v, dk, dv:
+ *             [batch, kv_heads, N, head_dim] (kv_heads = heads unless grouped
+ *             query attention is asked for); contiguous, head_dim fastest,
+ *             element type given by params->dtype, base pointers 16-byte
+ *             aligned.
  *             sel_idx: int32 [batch, heads, m, n_select].
  *             lse: fp32 [batch, heads, N], natural-log sum of
  *             exp(softmax_scale * q.k) over the attended keys.
@@ -52,7 +54,8 @@ extern "C" {
 enum {
     MOSAIC_BSA_OK = 0,
     MOSAIC_BSA_ERR_NULL = -1,      /* a required pointer is NULL */
-    MOSAIC_BSA_ERR_SHAPE = -2,     /* non-positive size, or tile does not divide grid */
+    MOSAIC_BSA_ERR_SHAPE = -2,     /* non-positive size, tile does not divide grid, or
+                                      kv_heads does not divide heads */
     MOSAIC_BSA_ERR_NSELECT = -3,   /* n_select < 0 or n_select > m - 1 */
     MOSAIC_BSA_ERR_HEAD_DIM = -4,  /* head_dim not in {32, 64, 128} */
     MOSAIC_BSA_ERR_DTYPE = -5,     /* dtype not MOSAIC_BSA_F32 / MOSAIC_BSA_BF16 */
@@ -77,6 +80,12 @@ typedef struct {
                                accumulation and softmax are fp32 in both cases */
     float softmax_scale;    /* <= 0 selects 1/sqrt(head_dim) (fine-grained
                                attention equation) */
+    int32_t kv_heads;       /* key/value heads for grouped query attention (the
+                               paper's Attention paragraph: queries attend to a
+                               number of shared key-value heads); 0 = heads.
+                               Must divide heads: query head a uses key/value
+                               head a / (heads / kv_heads).  Selection stays
+                               per query head. */
 } mosaic_bsa_params;
 
 /* Bytes of device workspace that `op` needs for `params`; 0 if none.
@@ -86,13 +95,15 @@ size_t mosaic_bsa_workspace_bytes(const mosaic_bsa_params *params, int op);
 /*
  * Block selection (pooling equation, block-level attention equation,
  * Selection paragraph).
- *   q, k      in   device, [B, heads, N, D]
+ *   q         in   device, [B, heads, N, D]
+ *   k         in   device, [B, kv_heads, N, D]
  *   sel_idx   out  device, int32 [B, heads, m, n]: for every query block the
  *                  n key blocks j != i with the largest pooled score, ordered
  *                  by (score descending, block index ascending).
  *   workspace      device scratch of mosaic_bsa_workspace_bytes(.., OP_SELECT)
- *                  bytes; on return it holds the pooled q then the pooled k,
- *                  fp32 [B, heads, m, D] each.
+ *                  bytes; on return it holds the pooled q, fp32
+ *                  [B, heads, m, D], at its start and the pooled k, fp32
+ *                  [B, kv_heads, m, D], at the start of its second half.
  * Arithmetic is fixed so that indices are reproducible bit for bit: pooled
  * sums are fp32 adds in in-tile row-major order followed by one multiply by
  * 1/b; a score is the fp32 chain acc = fma(qbar[d], kbar[d], acc), d ascending.

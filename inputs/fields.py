@@ -56,6 +56,7 @@ class GridConfig:
     sigma_white: float    # sigma_w
     sigma_member: float = 0.0   # sigma_m; > 0 means members share a base field
     with_dout: bool = False
+    kv_heads: int = 0           # key/value heads; 0 = heads (no grouping)
 
     @property
     def n_tokens(self) -> int:
@@ -92,6 +93,12 @@ CONFIGS = {
     # to measure what gathering 2-D tiles costs against contiguous blocks.
     6: GridConfig(6, 8, 16, 384, 128, 1, 128, 64, 24, "bf16", 6.0, 0.1),
     7: GridConfig(7, 8, 16, 192, 256, 8, 16, 64, 24, "bf16", 6.0, 0.1),
+    # Grouped query attention at the paper's ratio of 4 query heads per
+    # key/value head (architecture table): 8 is configuration 3 and 9 is
+    # configuration 6 with K and V of shape [B, heads / 4, N, D].
+    8: GridConfig(8, 24, 16, 120, 240, 8, 8, 64, 16, "bf16", 6.0, 0.1,
+                  sigma_member=0.05, kv_heads=4),
+    9: GridConfig(9, 8, 16, 384, 128, 1, 128, 64, 24, "bf16", 6.0, 0.1, kv_heads=4),
 }
 
 
@@ -168,10 +175,13 @@ def _finish(x: np.ndarray, cfg: GridConfig) -> np.ndarray:
 
 
 def make_tensor(cfg: GridConfig, name: str, workers: int = 8) -> np.ndarray:
-    """One of q/k/v/do for `cfg`: fp32 array [B, heads, N, D] (values
-    bf16-representable when cfg.dtype == "bf16")."""
+    """One of q/k/v/do for `cfg`: fp32 array [B, heads, N, D] ([B, kv_heads,
+    N, D] for k and v of a grouped configuration; values bf16-representable
+    when cfg.dtype == "bf16")."""
     seed = SEED_BASE + 100 * cfg.config_id + TENSOR_ID[name]
     B, h, N, D = cfg.batch, cfg.heads, cfg.n_tokens, cfg.head_dim
+    if name in ("k", "v") and cfg.kv_heads:
+        h = cfg.kv_heads
     out = np.empty((B, h, N, D), dtype=np.float32)
 
     if name == "do":   # upstream gradient: plain white noise

@@ -31,7 +31,8 @@ class _CParams(ctypes.Structure):
                 ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
                 ("block_h", ctypes.c_int32), ("block_w", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("n_select", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("kv_heads", ctypes.c_int32)]
 
 
 @dataclasses.dataclass
@@ -47,11 +48,12 @@ class Params:
     n_select: int
     dtype: int = BF16
     softmax_scale: float = 0.0
+    kv_heads: int = 0
 
     def c_struct(self) -> _CParams:
         return _CParams(self.batch, self.heads, self.grid_h, self.grid_w,
                         self.block_h, self.block_w, self.head_dim,
-                        self.n_select, self.dtype, self.softmax_scale)
+                        self.n_select, self.dtype, self.softmax_scale, self.kv_heads)
 
     @property
     def n_tokens(self) -> int:

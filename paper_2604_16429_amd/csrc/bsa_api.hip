@@ -12,7 +12,8 @@ namespace {
 struct Checked {
     bsa::Geom g;
     int D;
-    int64_t BH;
+    int64_t BH;       // batch * heads: query slices
+    int64_t BKV;      // batch * kv_heads: key/value slices
     bool is_bf16;
 };
 
@@ -35,9 +36,12 @@ int check_params(const mosaic_bsa_params* p, Checked* out)
         return MOSAIC_BSA_ERR_HEAD_DIM;
     if (p->dtype != MOSAIC_BSA_F32 && p->dtype != MOSAIC_BSA_BF16) return MOSAIC_BSA_ERR_DTYPE;
     if (p->n_select < 0 || p->n_select > m - 1) return MOSAIC_BSA_ERR_NSELECT;
+    const int kv_heads = p->kv_heads == 0 ? p->heads : p->kv_heads;
+    if (kv_heads < 0 || kv_heads > p->heads || p->heads % kv_heads) return MOSAIC_BSA_ERR_SHAPE;
 
     out->D = p->head_dim;
     out->BH = BH;
+    out->BKV = (int64_t)p->batch * kv_heads;
     out->is_bf16 = p->dtype == MOSAIC_BSA_BF16;
     bsa::Geom& g = out->g;
     g.heads = p->heads;
@@ -50,6 +54,7 @@ int check_params(const mosaic_bsa_params* p, Checked* out)
     g.n_select = p->n_select;
     g.n_tokens = N;
     g.scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+    g.kv_group = p->heads / kv_heads;
     return MOSAIC_BSA_OK;
 }
 

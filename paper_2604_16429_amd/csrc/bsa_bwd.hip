@@ -104,6 +104,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
     const int tau_q = rc * 64 + (threadIdx.x >> 2);
     const bool valid = tau_q < b;
     const int64_t base = bh_idx * g.n_tokens * D;
+    const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
     const int64_t tok_q = token_of(g, i, valid ? tau_q : 0);
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     const float c2 = g.scale * kLog2e;
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
         for (int k0 = 0; k0 < b; k0 += KC) {
             const int kcnt = min(KC, b - k0);
             __syncthreads();
-            stage_rows<T, D>(g, k, v, base, beta, k0, kcnt, k_s, v_s);
+            stage_rows<T, D>(g, k, v, kv_base, beta, k0, kcnt, k_s, v_s);
             __syncthreads();
             for (int t = 0; t < kcnt; ++t) {
                 const float* kr = k_s + t * D + quarter * CPT;
@@ -174,14 +175,16 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
     const int rc = blockIdx.x % row_chunks;
     const int64_t blk = blockIdx.x / row_chunks;
     const int j = (int)(blk % g.n_blocks);
-    const int64_t bh_idx = blk / g.n_blocks;
+    const int64_t kv_idx = blk / g.n_blocks;          // key/value slice
     const int b = g.block_tokens, n = g.n_select, m = g.n_blocks;
     const int quarter = threadIdx.x & 3;
     const int tau_k = rc * 64 + (threadIdx.x >> 2);
     const bool valid = tau_k < b;
-    const int64_t base = bh_idx * g.n_tokens * D;
+    const int64_t base = kv_idx * g.n_tokens * D;
     const int64_t tok_k = token_of(g, j, valid ? tau_k : 0);
-    const int32_t* sel_bh = sel_idx + bh_idx * (int64_t)m * n;
+    // the query slices that share this key/value slice are consecutive
+    const int64_t kv_heads = g.heads / g.kv_group;
+    const int64_t bh_first = (kv_idx / kv_heads) * g.heads + (kv_idx % kv_heads) * g.kv_group;
     const float c2 = g.scale * kLog2e;
 
     float kr[CPT], vr[CPT], acck[CPT], accv[CPT];
@@ -196,6 +199,12 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
     }
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // query heads in ascending order, then query blocks in ascending order:
+    // the summation order is fixed
+    for (int gq = 0; gq < g.kv_group; ++gq) {
+    const int64_t bh_idx = bh_first + gq;
+    const int64_t q_base = bh_idx * g.n_tokens * D;
+    const int32_t* sel_bh = sel_idx + bh_idx * (int64_t)m * n;
     for (int i0 = 0; i0 < m; i0 += SCAN) {
         // ---- which of the query blocks i0 .. i0+SCAN-1 attend to block j?
         // ascending order, so the summation order below is fixed
@@ -222,7 +231,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
             for (int r0 = 0; r0 < b; r0 += QC) {
                 const int qcnt = min(QC, b - r0);
                 __syncthreads();
-                stage_rows<T, D>(g, q, dout, base, i, r0, qcnt, q_s, g_s);
+                stage_rows<T, D>(g, q, dout, q_base, i, r0, qcnt, q_s, g_s);
                 if ((int)threadIdx.x < qcnt) {
                     const int64_t tok = token_of(g, i, r0 + threadIdx.x);
                     lse_s[threadIdx.x] = lse[bh_idx * g.n_tokens + tok] * kLog2e;
@@ -250,6 +259,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
                 }
             }
         }
+    }
     }
 
     if (valid) {
@@ -282,7 +292,8 @@ static hipError_t launch_bwd_t(const void* q, const void* k, const void* v, cons
                        row_chunks);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<T, D>), grid, dim3(256), 0, stream, (const T*)q,
+    dim3 grid_kv((unsigned)(BH / g.kv_group * g.n_blocks * row_chunks));
+    hipLaunchKernelGGL((bwd_dkdv_kernel<T, D>), grid_kv, dim3(256), 0, stream, (const T*)q,
                        (const T*)k, (const T*)v, (const T*)dout, lse, delta, sel_idx, (T*)dk,
                        (T*)dv, g, row_chunks);
     return hipGetLastError();

@@ -175,7 +175,7 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
                                         const float* __restrict__ delta,
                                         const int32_t* __restrict__ sel_idx,
                                         uint16_t* __restrict__ dq, const Geom& g,
-                                        int64_t slices_xcd)
+                                        uint32_t n_units)
 {
     constexpr int KS = D / 16, DT = D / 32;
     using IO = TileIO<D, NW>;
@@ -188,28 +188,19 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
     const int n = g.n_select;
     const int subs = g.block_tokens / 64;
 
-    // workgroup -> (slice, query block), slices dealt to the 8 XCDs whole
+    // workgroup -> (query slice, query block), key/value slices dealt to the 8
+    // XCDs whole
     int i;
     int64_t bh_idx;
-    {
-        const int64_t w = blockIdx.x;
-        const int64_t per_slice = g.n_blocks;
-        if (w < slices_xcd * per_slice) {
-            const int64_t seq = w >> 3;
-            bh_idx = (seq / per_slice) * 8 + (w & 7);
-            i = (int)(seq % per_slice);
-        } else {
-            bh_idx = w / per_slice;
-            i = (int)(w % per_slice);
-        }
-    }
+    map_workgroup(g, blockIdx.x, (uint32_t)g.n_blocks, n_units, bh_idx, i);
     const int64_t base = bh_idx * g.n_tokens * D;
+    const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
     const __amdgpu_buffer_rsrc_t k_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, slice_bytes, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + kv_base), 0, slice_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t v_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(v + base), 0, slice_bytes, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(v + kv_base), 0, slice_bytes, 0x00020000);
 
     IO io;
     io.init(g, lane, wave);
@@ -311,7 +302,7 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
                                           const float* __restrict__ delta,
                                           const int32_t* __restrict__ sel_idx,
                                           uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                          const Geom& g, int64_t slices_xcd)
+                                          const Geom& g, uint32_t n_units)
 {
     constexpr int KS = D / 16, DT = D / 32;
     constexpr bool DO_DV = (PASS & PASS_DV) != 0, DO_DK = (PASS & PASS_DK) != 0;
@@ -330,31 +321,20 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
     const int n = g.n_select, m = g.n_blocks;
     const int subs = g.block_tokens / 64;
 
+    // workgroup -> (key/value slice, key block), slices dealt to the 8 XCDs
+    // whole; the query slices that share the key/value slice are consecutive
     int j;
-    int64_t bh_idx;
+    int64_t base, bh_first;
     {
-        const int64_t w = blockIdx.x;
-        const int64_t per_slice = m;
-        if (w < slices_xcd * per_slice) {
-            const int64_t seq = w >> 3;
-            bh_idx = (seq / per_slice) * 8 + (w & 7);
-            j = (int)(seq % per_slice);
-        } else {
-            bh_idx = w / per_slice;
-            j = (int)(w % per_slice);
-        }
+        uint32_t unit, r;
+        map_unit(blockIdx.x, (uint32_t)m, n_units, unit, r);
+        j = (int)r;
+        base = (int64_t)unit * g.n_tokens * D;
+        const uint32_t kv_heads = (uint32_t)(g.heads / g.kv_group);
+        const uint32_t e = unit / kv_heads, a = unit - e * kv_heads;
+        bh_first = (int64_t)e * g.heads + (int64_t)a * g.kv_group;
     }
-    const int64_t base = bh_idx * g.n_tokens * D;
-    const int32_t* sel_bh = sel_idx + bh_idx * (int64_t)m * n;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
-    const __amdgpu_buffer_rsrc_t q_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(q + base), 0, slice_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t g_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(dout + base), 0, slice_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t l_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(lse2 + bh_idx * g.n_tokens), 0, (uint32_t)(g.n_tokens * 4), 0x00020000);
-    const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(delta + bh_idx * g.n_tokens), 0, (uint32_t)(g.n_tokens * 4), 0x00020000);
 
     IO io;
     io.init(g, lane, wave);
@@ -388,6 +368,20 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
         if constexpr (DO_DK) acck[dt] = zero_tile();
         if constexpr (DO_DV) accv[dt] = zero_tile();
     }
+
+    // query heads of the group in ascending order, query blocks in ascending
+    // order within each: the summation order is fixed
+    for (int gq = 0; gq < g.kv_group; ++gq) {
+    const int64_t bh_idx = bh_first + gq;
+    const int32_t* sel_bh = sel_idx + bh_idx * (int64_t)m * n;
+    const __amdgpu_buffer_rsrc_t q_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(q + bh_idx * g.n_tokens * D), 0, slice_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(dout + bh_idx * g.n_tokens * D), 0, slice_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t l_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(lse2 + bh_idx * g.n_tokens), 0, (uint32_t)(g.n_tokens * 4), 0x00020000);
+    const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(delta + bh_idx * g.n_tokens), 0, (uint32_t)(g.n_tokens * 4), 0x00020000);
 
     // items of a round: (connected query block e, sub-tile ct), e-major
     auto issue_item = [&](int item, int buf) {
@@ -489,6 +483,7 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
             }
         }
     }
+    }
 
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
@@ -548,25 +543,25 @@ __global__ __launch_bounds__(256) void bwd_mfma_prep_kernel(const uint16_t* __re
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dq_d##D##_w##NW(                       \
         const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
         const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dq, Geom g,      \
-        int64_t slices_xcd)                                                                       \
+        uint32_t n_units)                                                                       \
     {                                                                                             \
-        bwdm::dq_body<D, NW>(q, k, v, dout, lse2, delta, sel_idx, dq, g, slices_xcd);             \
+        bwdm::dq_body<D, NW>(q, k, v, dout, lse2, delta, sel_idx, dq, g, n_units);             \
     }                                                                                             \
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dv_d##D##_w##NW(                       \
         const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
         const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
-        uint16_t* dv, Geom g, int64_t slices_xcd)                                                 \
+        uint16_t* dv, Geom g, uint32_t n_units)                                                 \
     {                                                                                             \
         bwdm::dkdv_body<D, NW, bwdm::PASS_DV>(q, k, v, dout, lse2, delta, sel_idx, dk, dv, g,     \
-                                              slices_xcd);                                        \
+                                              n_units);                                        \
     }                                                                                             \
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dk_d##D##_w##NW(                       \
         const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
         const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
-        uint16_t* dv, Geom g, int64_t slices_xcd)                                                 \
+        uint16_t* dv, Geom g, uint32_t n_units)                                                 \
     {                                                                                             \
         bwdm::dkdv_body<D, NW, bwdm::PASS_DK>(q, k, v, dout, lse2, delta, sel_idx, dk, dv, g,     \
-                                              slices_xcd);                                        \
+                                              n_units);                                        \
     }
 BSA_BWD_KERNELS(64, 2)
 BSA_BWD_KERNELS(64, 4)
@@ -576,10 +571,10 @@ BSA_BWD_KERNELS(64, 8)
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dkdv_d64_w##NW(                        \
         const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
         const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
-        uint16_t* dv, Geom g, int64_t slices_xcd)                                                 \
+        uint16_t* dv, Geom g, uint32_t n_units)                                                 \
     {                                                                                             \
         bwdm::dkdv_body<64, NW, bwdm::PASS_DV | bwdm::PASS_DK>(q, k, v, dout, lse2, delta,        \
-                                                               sel_idx, dk, dv, g, slices_xcd);   \
+                                                               sel_idx, dk, dv, g, n_units);   \
     }
 BSA_BWD_FUSED(2)
 BSA_BWD_FUSED(4)
@@ -620,19 +615,19 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int nw = g.block_tokens / 32;
-    const dim3 grid((unsigned)(BH * g.n_blocks)), block(64 * nw);
-    const int64_t sx = BH - BH % 8;
+    const uint32_t sx = (uint32_t)(BH / g.kv_group);           // key/value slices
+    const dim3 grid((unsigned)(BH * g.n_blocks)), grid_kv(sx * (unsigned)g.n_blocks), block(64 * nw);
 #define BSA_LAUNCH(D_, NW_)                                                                       \
     if (D == D_ && nw == NW_) {                                                                   \
         bwd_mfma_dq_d##D_##_w##NW_<<<grid, block, 0, stream>>>(                                   \
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
             lse2, delta, sel_idx, (uint16_t*)dq, g, sx);                                          \
         if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
-        bwd_mfma_dv_d##D_##_w##NW_<<<grid, block, 0, stream>>>(                                   \
+        bwd_mfma_dv_d##D_##_w##NW_<<<grid_kv, block, 0, stream>>>(                                   \
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
             lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
         if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
-        bwd_mfma_dk_d##D_##_w##NW_<<<grid, block, 0, stream>>>(                                   \
+        bwd_mfma_dk_d##D_##_w##NW_<<<grid_kv, block, 0, stream>>>(                                   \
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
             lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
         return hipGetLastError();                                                                 \
@@ -643,7 +638,7 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
             lse2, delta, sel_idx, (uint16_t*)dq, g, sx);                                          \
         if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
-        bwd_mfma_dkdv_d64_w##NW_<<<grid, block, 0, stream>>>(                                     \
+        bwd_mfma_dkdv_d64_w##NW_<<<grid_kv, block, 0, stream>>>(                                     \
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
             lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
         return hipGetLastError();                                                                 \

@@ -20,7 +20,56 @@ struct Geom {
     int32_t n_select;     // n
     int64_t n_tokens;     // N
     float   scale;        // softmax scale
+    int32_t kv_group;     // query heads per key/value head (1 = every head has its own)
 };
+
+// [N, D] slice of K and V that the query slice bh = batch * heads + head
+// attends to (grouped query attention: consecutive query heads share one).
+__device__ __forceinline__ int64_t kv_slice_of(const Geom& g, int64_t bh)
+{
+    if (g.kv_group == 1) return bh;
+    const int64_t e = bh / g.heads, a = bh - e * g.heads;
+    return e * (g.heads / g.kv_group) + a / g.kv_group;
+}
+
+// Workgroup id -> (query slice, item).  Workgroup ids go round-robin over the
+// 8 XCDs, each with its own L2, so key/value slices are dealt to XCDs whole:
+// key/value slice u runs on XCD u % 8, the items of the query heads that share
+// it back to back; the K/V tiles that those query blocks gather are then
+// fetched into one L2 instead of eight.  The last (number of key/value slices
+// % 8) slices use the plain linear order.  per_slice: items per query slice;
+// n_units: number of key/value slices.  The grid is n_units * kv_group *
+// per_slice workgroups, which the launcher keeps below 2^32.
+__device__ __forceinline__ void map_unit(uint32_t w, uint32_t per_unit, uint32_t n_units,
+                                         uint32_t& unit, uint32_t& r)
+{
+    const uint32_t units_xcd = n_units & ~7u;
+    if (w < units_xcd * per_unit) {
+        const uint32_t seq = w >> 3, round = seq / per_unit;
+        unit = round * 8 + (w & 7);
+        r = seq - round * per_unit;
+    } else {
+        unit = w / per_unit;
+        r = w - unit * per_unit;
+    }
+}
+
+__device__ __forceinline__ void map_workgroup(const Geom& g, uint32_t w, uint32_t per_slice,
+                                              uint32_t n_units, int64_t& bh, int& item)
+{
+    uint32_t unit, r;
+    map_unit(w, per_slice * (uint32_t)g.kv_group, n_units, unit, r);
+    if (g.kv_group == 1) {
+        bh = unit;
+        item = (int)r;
+        return;
+    }
+    const uint32_t head_in_group = r / per_slice;
+    item = (int)(r - head_in_group * per_slice);
+    const uint32_t kv_heads = (uint32_t)(g.heads / g.kv_group);
+    const uint32_t e = unit / kv_heads, a = unit - e * kv_heads;
+    bh = (int64_t)e * g.heads + a * g.kv_group + head_in_group;
+}
 
 // Token index (inside one [N, D] slice) of in-tile position tau of block beta:
 // the tile partition of the grid (Compression paragraph, with tiles as blocks).

@@ -36,6 +36,7 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(
     const int tau_q = rc * 64 + threadIdx.x;
     const bool valid = tau_q < b;
     const int64_t base = bh_idx * g.n_tokens * D;
+    const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
     const int64_t tok_q = token_of(g, i, valid ? tau_q : 0);
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     const float scale2 = g.scale * 1.4426950408889634f;   // to base-2 exponent
@@ -58,8 +59,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(
             for (int item = threadIdx.x; item < kcnt * (D / 4); item += 64) {
                 const int t = item / (D / 4), d = (item - t * (D / 4)) * 4;
                 const int64_t tok = token_of(g, beta, k0 + t);
-                *(float4*)(k_s + t * D + d) = load4(k + base + tok * D + d);
-                *(float4*)(v_s + t * D + d) = load4(v + base + tok * D + d);
+                *(float4*)(k_s + t * D + d) = load4(k + kv_base + tok * D + d);
+                *(float4*)(v_s + t * D + d) = load4(v + kv_base + tok * D + d);
             }
             __syncthreads();
 

@@ -198,7 +198,7 @@ template <int NW>
 __device__ __forceinline__ void fwd_mfma_d64_body(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
-    uint16_t* __restrict__ out, float* __restrict__ lse, const Geom& g, int64_t slices_xcd,
+    uint16_t* __restrict__ out, float* __restrict__ lse, const Geom& g, uint32_t n_units,
     int subs)
 {
     constexpr int D = 64;
@@ -223,42 +223,31 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     const int l32 = lane & 31, half = lane >> 5;
     const int n = g.n_select;
 
-    // Work item -> (batch*head slice, query block).  Workgroups are handed to
-    // the 8 XCDs round-robin by id; each XCD has its own L2.  Slices are dealt
-    // to XCDs whole (slice s runs on XCD s % 8, its query blocks back to back),
-    // so the K/V tiles a slice's query blocks share are fetched into one L2
-    // instead of eight.  The last BH % 8 slices use the plain linear order.
-    // A work item is NW consecutive sub-blocks of 64 queries of one query
-    // block (NW divides subs): item = block * (subs / NW) + group.
+    // Work item -> (query slice, query block); key/value slices are dealt to
+    // the XCDs whole (map_workgroup).  A work item is NW consecutive
+    // sub-blocks of 64 queries of one query block (NW divides subs):
+    // item = block * (subs / NW) + group.
     int i, qsub;
     int64_t bh_idx;
     {
-        const int64_t w = blockIdx.x;
         const int groups = subs / NW;
-        const int64_t per_slice = (int64_t)g.n_blocks * groups;
-        int64_t item;
-        if (w < slices_xcd * per_slice) {
-            const int64_t seq = w >> 3;
-            bh_idx = (seq / per_slice) * 8 + (w & 7);
-            item = seq % per_slice;
-        } else {
-            bh_idx = w / per_slice;
-            item = w % per_slice;
-        }
-        i = (int)(item / groups);
-        qsub = (int)(item - (int64_t)i * groups) * NW + wave;
+        int item;
+        map_workgroup(g, blockIdx.x, (uint32_t)(g.n_blocks * groups), n_units, bh_idx, item);
+        i = item / groups;
+        qsub = (item - i * groups) * NW + wave;
     }
     const int64_t base = bh_idx * g.n_tokens * D;
+    const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     q += base; out += base;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
     const __amdgpu_buffer_rsrc_t k_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, slice_bytes, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + kv_base), 0, slice_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t v_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(v + base), 0, slice_bytes, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(v + kv_base), 0, slice_bytes, 0x00020000);
     // zero records: every access is out of range, the load moves nothing
     const __amdgpu_buffer_rsrc_t null_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, 0, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + kv_base), 0, 0, 0x00020000);
 
     // Visiting order: the own block first (it needs nothing from sel_idx, so
     // its gathers start at once), then the selected blocks in ascending block
@@ -539,10 +528,10 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     __global__ __launch_bounds__(64 * NW, 2) void NAME(                                           \
         const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,                           \
         const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,                      \
-        uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd,          \
+        uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, uint32_t n_units,            \
         int subs)                                                                                 \
     {                                                                                             \
-        fwd_mfma_d64_body<NW>(q, k, v, sel_idx, out, lse, g, slices_xcd, subs);                   \
+        fwd_mfma_d64_body<NW>(q, k, v, sel_idx, out, lse, g, n_units, subs);                      \
     }
 BSA_FWD_D64_KERNEL(fwd_mfma_b64_d64_kernel, 1)
 BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg2_kernel, 2)
@@ -574,7 +563,7 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const in
                   : nw == 2 ? fwd_mfma_d64_wg2_kernel : fwd_mfma_b64_d64_kernel;
     kernel<<<grid, dim3(64 * nw), 0, stream>>>((const uint16_t*)q, (const uint16_t*)k,
                                                (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
-                                               (int64_t)(BH - BH % 8), subs);
+                                               (uint32_t)(BH / g.kv_group), subs);
     return hipGetLastError();
 }
 

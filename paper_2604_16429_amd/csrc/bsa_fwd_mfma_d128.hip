@@ -70,7 +70,7 @@ constexpr int NW = 4;
 __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
-    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, int64_t slices_xcd)
+    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, uint32_t n_units)
 {
     using namespace d128;
     static_assert(NW == 2 || NW == 4 || NW == 8, "a half tile is 8 loads, split between waves");
@@ -87,34 +87,23 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     const int n = g.n_select;
     const int subs = g.block_tokens / 64;          // 64-key sub-tiles per attended block
 
-    // Workgroup -> (batch*head slice, query block): slices are dealt to the 8
-    // XCDs whole (workgroup ids go round-robin over the XCDs, each with its own
-    // L2), the last BH % 8 slices use the plain linear order.
+    // Workgroup -> (query slice, query block); key/value slices are dealt to
+    // the XCDs whole (map_workgroup).
     int i;
     int64_t bh_idx;
-    {
-        const int64_t w = blockIdx.x;
-        const int64_t per_slice = g.n_blocks;
-        if (w < slices_xcd * per_slice) {
-            const int64_t seq = w >> 3;
-            bh_idx = (seq / per_slice) * 8 + (w & 7);
-            i = (int)(seq % per_slice);
-        } else {
-            bh_idx = w / per_slice;
-            i = (int)(w % per_slice);
-        }
-    }
+    map_workgroup(g, blockIdx.x, (uint32_t)g.n_blocks, n_units, bh_idx, i);
     const int64_t base = bh_idx * g.n_tokens * D;
+    const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
     const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
     q += base; out += base;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
     const __amdgpu_buffer_rsrc_t k_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, slice_bytes, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + kv_base), 0, slice_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t v_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(v + base), 0, slice_bytes, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(v + kv_base), 0, slice_bytes, 0x00020000);
     // zero records: every access is out of range, the load moves nothing
     const __amdgpu_buffer_rsrc_t null_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(k + base), 0, 0, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(k + kv_base), 0, 0, 0x00020000);
 
     // Visiting order: own block first, then the selected blocks in ascending
     // block order when they fit one wavefront (workgroups that run together on
@@ -482,7 +471,7 @@ hipError_t launch_fwd_mfma_d128(const void* q, const void* k, const void* v,
     dim3 grid((unsigned)(BH * g.n_blocks));
     fwd_mfma_d128_kernel<<<grid, dim3(64 * NW), 0, stream>>>(
         (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
-        (int64_t)(BH - BH % 8));
+        (uint32_t)(BH / g.kv_group));
     return hipGetLastError();
 }
 

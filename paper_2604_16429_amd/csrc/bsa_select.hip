@@ -33,9 +33,10 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
                                                    float* __restrict__ kbar, Geom g, int D,
                                                    int64_t BH, int wgs_per_slice)
 {
-    // blockIdx.x = (tensor * BH + batch*head) * wgs_per_slice + chunk of 256 items
+    // blockIdx.x = slice * wgs_per_slice + chunk of 256 items; slices: the BH
+    // query slices, then the key slices (fewer under grouped query attention)
     const int chunk = blockIdx.x % wgs_per_slice;
-    int64_t bh_idx = blockIdx.x / wgs_per_slice;     // tensor * BH + batch*head
+    int64_t bh_idx = blockIdx.x / wgs_per_slice;
     const bool is_k = bh_idx >= BH;
     if (is_k) bh_idx -= BH;
     const T* __restrict__ x = is_k ? k : q;
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
     const int i0 = (int)(blockIdx.x - bh_idx * groups) * G;
     const int rows = min(G, m - i0);
     qbar += (bh_idx * m + i0) * D;
-    kbar += bh_idx * m * D;
+    kbar += kv_slice_of(g, bh_idx) * m * D;
 
     for (int e = threadIdx.x; e < rows * D; e += blockDim.x) q_s[e] = qbar[e];
     __syncthreads();
@@ -266,7 +267,7 @@ static hipError_t launch_pool_t(const void* q, const void* k, float* qbar, float
 {
     const int items = g.n_blocks * (D / VEC);
     const int wgs_per_slice = (items + 255) / 256;
-    dim3 grid((unsigned)(2 * BH * wgs_per_slice));
+    dim3 grid((unsigned)((BH + BH / g.kv_group) * wgs_per_slice));
     hipLaunchKernelGGL((pool_kernel<T, VEC>), grid, dim3(256), 0, stream, (const T*)q,
                        (const T*)k, qbar, kbar, g, D, BH, wgs_per_slice);
     return hipGetLastError();

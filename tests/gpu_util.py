@@ -14,7 +14,7 @@ def params_of(cfg, n_select=None, softmax_scale=0.0):
                     cfg.block_w, cfg.head_dim,
                     cfg.n_select if n_select is None else n_select,
                     binding.BF16 if cfg.dtype == "bf16" else binding.F32,
-                    softmax_scale)
+                    softmax_scale, getattr(cfg, "kv_heads", 0))
 
 
 def to_dev(x, cfg):
@@ -63,7 +63,7 @@ def gpu_bwd(cfg, q, k, v, dout, idx, n_select=None, softmax_scale=0.0):
     idx_d = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).to("cuda")
     q_d, k_d, v_d, do_d = (to_dev(x, cfg) for x in (q, k, v, dout))
     out, lse = fwd_dev(cfg, q_d, k_d, v_d, idx_d, n_select, softmax_scale)
-    dq, dk, dv = (torch.full_like(q_d, float("nan")) for _ in range(3))
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q_d, k_d, v_d))
     ws = torch.empty(max(M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD), 256),
                      dtype=torch.uint8, device="cuda")
     M.mosaic_bsa_bwd(p, q_d, k_d, v_d, out, lse, do_d, idx_d, dq, dk, dv, ws)

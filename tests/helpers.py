@@ -7,8 +7,9 @@ import numpy as np
 
 
 def shape_ns(batch, heads, grid_h, grid_w, block_h, block_w, head_dim, n_select,
-             dtype="fp32"):
+             dtype="fp32", kv_heads=0):
     return types.SimpleNamespace(
+        kv_heads=kv_heads,
         batch=batch, heads=heads, grid_h=grid_h, grid_w=grid_w, block_h=block_h,
         block_w=block_w, head_dim=head_dim, n_select=n_select, dtype=dtype,
         n_tokens=grid_h * grid_w, block_tokens=block_h * block_w,

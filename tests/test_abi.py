@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(binding._CParams) == 40
+    assert ctypes.sizeof(binding._CParams) == 44
 
 
 def test_workspace_bytes():
@@ -54,6 +54,7 @@ def test_workspace_bytes():
     (dict(block_h=0), -2), (dict(block_h=32, block_w=64), -2),   # b > 1024
     (dict(n_select=-1), -3), (dict(n_select=32), -3),
     (dict(head_dim=48), -4), (dict(dtype=7), -5),
+    (dict(kv_heads=3), -2), (dict(kv_heads=4), -2), (dict(kv_heads=-1), -2),   # heads = 2
 ])
 def test_bad_params_are_rejected_before_any_launch(kw, code):
     p = good(**kw)

@@ -340,3 +340,35 @@ def test_backward_gradient_configuration_fields(G, oracle):
     again = G.gpu_bwd(cfg, p.q, p.k, p.v, p.dout, idx)
     for a, b in zip(got, again):
         assert np.array_equal(a, b)
+
+
+# --------------------------------------------------------------------------
+# grouped query attention: shared key/value heads, selection per query head
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,B,heads,kv_heads,H,W,bh,bw,D,n", [
+    ("fp32", 2, 4, 2, 16, 32, 8, 8, 32, 3),      # general kernels
+    ("bf16", 2, 6, 2, 12, 18, 6, 6, 64, 2),      # general kernels, bf16, b = 36
+    ("bf16", 3, 6, 2, 16, 32, 8, 8, 64, 3),      # head dim 64 matrix-core path, 6 kv slices
+    ("bf16", 5, 4, 2, 16, 32, 8, 8, 64, 3),      # 10 kv slices: 8 dealt to XCDs, 2 linear
+    ("bf16", 1, 8, 1, 32, 32, 16, 16, 64, 2),    # 256-token blocks, one shared kv head
+    ("bf16", 3, 8, 4, 16, 64, 8, 16, 128, 3),    # head dim 128 matrix-core path, 12 kv slices
+    ("bf16", 2, 4, 4, 16, 32, 8, 8, 64, 3),      # kv_heads = heads, given explicitly
+])
+def test_grouped_query_attention(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n):
+    cfg = shape_ns(B, heads, H, W, bh, bw, D, n, dtype, kv_heads=kv_heads)
+    rng = np.random.default_rng(7000 + B + heads + D)
+    q, dout = (rng.standard_normal((B, heads, H * W, D)).astype(np.float32) for _ in range(2))
+    k, v = (rng.standard_normal((B, kv_heads, H * W, D)).astype(np.float32) for _ in range(2))
+    if dtype == "bf16":
+        q, k, v, dout = (round_to_bf16(x) for x in (q, k, v, dout))
+    s = oracle.shape_of(cfg)
+    idx_ref = oracle.select_gqa(s, q, k)
+    idx_gpu = G.gpu_select(cfg, q, k)
+    assert np.array_equal(idx_gpu, idx_ref)
+    out_ref, lse_ref = oracle.fwd_gqa(s, q, k, v, idx_ref)
+    out_gpu, lse_gpu = G.gpu_fwd(cfg, q, k, v, idx_gpu)
+    check_out(cfg, out_gpu, lse_gpu, out_ref, lse_ref)
+    ref = oracle.bwd_gqa(s, q, k, v, dout, idx_ref)
+    got = G.gpu_bwd(cfg, q, k, v, dout, idx_ref)
+    assert got[1].shape == k.shape and got[2].shape == v.shape
+    check_grads(cfg, got, ref)
