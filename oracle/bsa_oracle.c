@@ -271,6 +271,89 @@ void oracle_block_weights(const oracle_shape *s, const float *q, const float *k,
     free(z);
 }
 
+/* ---- the paper's three branches (Block-Sparse Attention subsection) -------
+ * The single-softmax path above is one reading; the subsection itself keeps
+ * three branches with a softmax each, summed with gates (the aggregation
+ * equation of the Native Sparse Attention subsection).  The two C routines
+ * below are their building blocks; oracle/bsa_oracle.py composes them.
+ */
+
+/* Selection paragraph, taken literally: the top-n entries of row i of the
+ * block-level attention over ALL m key blocks (the block itself is a
+ * candidate), ordered by (score descending, index ascending); 1 <= n <= m. */
+void oracle_select_all_from_pooled(const oracle_shape *s, const float *qbar, const float *kbar,
+                                   int32_t *sel_idx /* [B*h, m, n] */)
+{
+    const int D = s->head_dim, m = n_blocks(s), n = s->n_select;
+    const int64_t BH = (int64_t)s->batch * s->heads;
+#pragma omp parallel
+    {
+        cand *row = (cand *)malloc(sizeof(cand) * (size_t)(m > 0 ? m : 1));
+#pragma omp for collapse(2) schedule(static)
+        for (int64_t g = 0; g < BH; ++g)
+            for (int i = 0; i < m; ++i) {
+                for (int j = 0; j < m; ++j) {
+                    row[j].score = block_score(qbar + (g * m + i) * D, kbar + (g * m + j) * D, D);
+                    row[j].index = j;
+                }
+                qsort(row, (size_t)m, sizeof(cand), cand_before);
+                for (int r = 0; r < n; ++r)
+                    sel_idx[(g * m + i) * n + r] = row[r].index;
+            }
+        free(row);
+    }
+}
+
+/* Fine-grained attention equation with an explicit block list: every token l
+ * of query block i attends, in one softmax with normaliser Z_l, to exactly
+ * the tokens of the cnt blocks lists[g, i, 0..cnt-1] (nothing is added to the
+ * list).  With the selected blocks this is the selection branch; with the
+ * blocks of a large local block it is the local branch. */
+void oracle_attend_lists(const oracle_shape *s, const float *q, const float *k, const float *v,
+                         const int32_t *lists /* [B*h, m, cnt] */, int cnt, double scale,
+                         double *out /* [B*h, N, D] */, double *lse /* [B*h, N] or NULL */)
+{
+    const int m = n_blocks(s), b = block_tokens(s), D = s->head_dim;
+    const int64_t BH = (int64_t)s->batch * s->heads, N = n_tokens(s);
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)s->head_dim);
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)cnt * b);
+#pragma omp for collapse(2) schedule(dynamic, 4)
+        for (int64_t g = 0; g < BH; ++g)
+            for (int i = 0; i < m; ++i) {
+                const int32_t *list = lists + (g * m + i) * cnt;
+                for (int tq = 0; tq < b; ++tq) {
+                    const int64_t l = token_of(s, i, tq);
+                    const float *ql = q + (g * N + l) * D;
+                    double M = -INFINITY, Z = 0.0;
+                    for (int c = 0; c < cnt; ++c)
+                        for (int tau = 0; tau < b; ++tau) {
+                            const float *kt = k + (g * N + token_of(s, list[c], tau)) * D;
+                            double dot = 0.0;
+                            for (int d = 0; d < D; ++d) dot += (double)ql[d] * (double)kt[d];
+                            z[c * b + tau] = scale * dot;
+                            if (z[c * b + tau] > M) M = z[c * b + tau];
+                        }
+                    for (int t = 0; t < cnt * b; ++t) {
+                        z[t] = exp(z[t] - M);
+                        Z += z[t];
+                    }
+                    double *ol = out + (g * N + l) * D;
+                    for (int d = 0; d < D; ++d) ol[d] = 0.0;
+                    for (int c = 0; c < cnt; ++c)
+                        for (int tau = 0; tau < b; ++tau) {
+                            const float *vt = v + (g * N + token_of(s, list[c], tau)) * D;
+                            const double p = z[c * b + tau] / Z;
+                            for (int d = 0; d < D; ++d) ol[d] += p * (double)vt[d];
+                        }
+                    if (lse) lse[g * N + l] = M + log(Z);
+                }
+            }
+        free(z);
+    }
+}
+
 /* ---- backward with the selection held fixed -------------------------------
  * With P the attention weights of the forward pass:
  *   delta_l = sum_d dO_l[d] O_l[d]

@@ -48,21 +48,25 @@ def _load():
     return _lib
 
 
-def _shape(batch, heads, grid_h, grid_w, block_h, block_w, head_dim, n_select):
+def _shape(batch, heads, grid_h, grid_w, block_h, block_w, head_dim, n_select,
+           own_is_candidate=False):
     if grid_h % block_h or grid_w % block_w:
         raise ValueError("tile must divide the grid")
     m = (grid_h // block_h) * (grid_w // block_w)
-    if not 0 <= n_select <= m - 1:
+    if own_is_candidate:          # three-branch form: top-n over all m blocks
+        if not 1 <= n_select <= m:
+            raise ValueError("n_select must be in [1, m]")
+    elif not 0 <= n_select <= m - 1:
         raise ValueError("n_select must be in [0, m-1]")
     return _Shape(batch, heads, grid_h, grid_w, block_h, block_w, head_dim,
                   n_select)
 
 
-def shape_of(cfg, n_select=None):
+def shape_of(cfg, n_select=None, own_is_candidate=False):
     """oracle shape from any object with the grid-configuration attributes."""
     return _shape(cfg.batch, cfg.heads, cfg.grid_h, cfg.grid_w, cfg.block_h,
                   cfg.block_w, cfg.head_dim,
-                  cfg.n_select if n_select is None else n_select)
+                  cfg.n_select if n_select is None else n_select, own_is_candidate)
 
 
 def _f32(x):
@@ -271,3 +275,112 @@ def bwd_gqa(s, q, k, v, dout, sel_idx, scale: float = 0.0):
     dq, dk, dv = bwd(s, q, expand_kv(k, s.heads), expand_kv(v, s.heads), dout,
                      sel_idx, scale)
     return dq, reduce_kv(dk, kv_heads), reduce_kv(dv, kv_heads)
+
+
+# ---------------------------------------------------------------------------
+# The paper's three branches (Block-Sparse Attention subsection), summed with
+# caller-supplied gate values (aggregation equation of the Native Sparse
+# Attention subsection).  Readings taken where the text leaves a choice:
+#   * coarse branch: softmax over ALL m blocks of qbar_i . kbar_j / sqrt(d_k)
+#     (the printed sum runs over l = 1..m, own block included), applied to the
+#     mean-pooled values, the result handed to every token of the block;
+#   * selection branch: top-n of that row over all m blocks (own block is a
+#     candidate), ranked by the raw pooled dot product (same order), then ONE
+#     softmax over the tokens of the selected blocks only;
+#   * local branch: plain attention inside "large blocks": aligned groups of
+#     local_h x local_w mesh tiles;
+#   * gates: values g[B, heads, N, 3] in the order (coarse, selection, local),
+#     one scalar per token, head and branch; how they are produced from the
+#     layer input is outside the path.
+# ---------------------------------------------------------------------------
+def select_all(s, q, k):
+    """Top-n key blocks per query block over all m blocks, int32 [B,h,m,n]."""
+    B, h, N, D, b, m = _dims(s)
+    if not 1 <= s.n_select <= m:
+        raise ValueError("three-branch selection needs 1 <= n <= m")
+    qbar, pq = _f32(pool(s, q))
+    kbar, pk = _f32(pool(s, k))
+    idx = np.empty((B, h, m, s.n_select), dtype=np.int32)
+    _load().oracle_select_all_from_pooled(ctypes.byref(s), pq, pk,
+                                          idx.ctypes.data_as(ctypes.c_void_p))
+    return idx
+
+
+def attend_lists(s, q, k, v, lists, scale: float = 0.0):
+    """One softmax per token over exactly the listed blocks of its query block;
+    lists int32 [B, h, m, cnt].  Returns (out, lse) float64."""
+    B, h, N, D, b, m = _dims(s)
+    q, pq = _f32(q)
+    k, pk = _f32(k)
+    v, pv = _f32(v)
+    _check(s, q, k, v)
+    lists, pl = _i32(lists)
+    cnt = lists.shape[-1]
+    assert lists.shape == (B, h, m, cnt) and cnt >= 1
+    assert lists.min() >= 0 and lists.max() < m
+    out = np.empty((B, h, N, D), dtype=np.float64)
+    lse = np.empty((B, h, N), dtype=np.float64)
+    _load().oracle_attend_lists(ctypes.byref(s), pq, pk, pv, pl, ctypes.c_int(cnt),
+                                ctypes.c_double(scale),
+                                out.ctypes.data_as(ctypes.c_void_p),
+                                lse.ctypes.data_as(ctypes.c_void_p))
+    return out, lse
+
+
+def local_lists(s, local_h: int, local_w: int):
+    """Blocks of the large local block that contains block i, ascending;
+    int32 [m, local_h*local_w].  Large blocks are aligned groups of
+    local_h x local_w mesh tiles."""
+    rows, cols = s.grid_h // s.block_h, s.grid_w // s.block_w
+    if rows % local_h or cols % local_w:
+        raise ValueError("the local group must divide the grid of tiles")
+    out = np.empty((rows * cols, local_h * local_w), dtype=np.int32)
+    for r in range(rows):
+        for c in range(cols):
+            r0, c0 = r - r % local_h, c - c % local_w
+            out[r * cols + c] = [(r0 + dr) * cols + (c0 + dc)
+                                 for dr in range(local_h) for dc in range(local_w)]
+    return out
+
+
+def coarse(s, q, k, v, scale: float = 0.0):
+    """Coarse-grained branch: (block outputs float64 [B,h,m,D], block-level
+    attention float64 [B,h,m,m]).  Pooled means are the fp32 ones of pool()."""
+    D = s.head_dim
+    qbar = pool(s, q).astype(np.float64)
+    kbar = pool(s, k).astype(np.float64)
+    vbar = pool(s, v).astype(np.float64)
+    sc = scale if scale > 0 else 1.0 / np.sqrt(D)
+    z = sc * np.einsum("ghid,ghjd->ghij", qbar, kbar)
+    z -= z.max(axis=-1, keepdims=True)
+    a = np.exp(z)
+    a /= a.sum(axis=-1, keepdims=True)
+    return np.einsum("ghij,ghjd->ghid", a, vbar), a
+
+
+def block_of_token(s):
+    """Block index of every token, int64 [N] (inverse of token_of)."""
+    B, h, N, D, b, m = _dims(s)
+    out = np.empty(N, dtype=np.int64)
+    for beta in range(m):
+        for tau in range(b):
+            out[token_of(s, beta, tau)] = beta
+    return out
+
+
+def fwd_three_branch(s, q, k, v, gates, local_h: int, local_w: int, scale: float = 0.0):
+    """out = g_cg * o_cg + g_fg * o_fg + g_l * o_l, float64 [B,h,N,D]; also
+    returns the selection and the three branch outputs.  k, v may carry fewer
+    heads than q (grouped query attention)."""
+    k, v = expand_kv(k, s.heads), expand_kv(v, s.heads)
+    B, h, N, D, b, m = _dims(s)
+    gates = np.asarray(gates, dtype=np.float64)
+    assert gates.shape == (B, h, N, 3)
+    o_blocks, _ = coarse(s, q, k, v, scale)
+    o_cg = o_blocks[:, :, block_of_token(s), :]
+    sel = select_all(s, q, k)
+    o_fg, _ = attend_lists(s, q, k, v, sel, scale)
+    win = np.broadcast_to(local_lists(s, local_h, local_w), (B, h, m, local_h * local_w))
+    o_l, _ = attend_lists(s, q, k, v, win, scale)
+    out = gates[..., 0:1] * o_cg + gates[..., 1:2] * o_fg + gates[..., 2:3] * o_l
+    return out, sel, (o_cg, o_fg, o_l)

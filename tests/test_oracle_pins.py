@@ -467,3 +467,128 @@ def test_gqa_with_one_head_per_group_is_the_plain_path(oracle):
     assert np.array_equal(oracle.select_gqa(s, q, k), idx)
     np.testing.assert_array_equal(oracle.fwd_gqa(s, q, k, v, idx)[0],
                                   oracle.fwd(s, q, k, v, idx)[0])
+
+
+# --------------------------------------------------------------------------
+# the three branches and their gated sum (Block-Sparse Attention subsection;
+# aggregation equation of the Native Sparse Attention subsection)
+# --------------------------------------------------------------------------
+def test_coarse_branch_with_single_token_blocks_is_dense_attention(oracle):
+    c = shape_ns(1, 2, 4, 6, 1, 1, 8, 1)
+    s = oracle.shape_of(c, own_is_candidate=True)
+    q, k, v = rand_qkv(c, 50)
+    o_blocks, a = oracle.coarse(s, q, k, v)
+    np.testing.assert_allclose(o_blocks, _sdpa(q, k, v), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(a.sum(-1), 1.0, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(oracle.coarse(s, q, k, v, scale=0.3)[0],
+                               _sdpa(q, k, v, scale=0.3), rtol=0, atol=1e-12)
+
+
+def test_coarse_branch_is_library_attention_of_the_tile_means(oracle):
+    c = shape_ns(2, 2, 8, 12, 4, 3, 8, 1)
+    s = oracle.shape_of(c, own_is_candidate=True)
+    q, k, v = rand_qkv(c, 51)
+    qb, kb, vb = (to_tiles(x, c).astype(np.float64).mean(axis=3) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(qb), torch.from_numpy(kb), torch.from_numpy(vb),
+        scale=1.0 / np.sqrt(8.0)).numpy()       # scale uses d_k, not the block size
+    np.testing.assert_allclose(oracle.coarse(s, q, k, v)[0], ref, rtol=0, atol=2e-6)
+
+
+def test_select_all_ranks_every_block_own_included(oracle):
+    c = shape_ns(1, 2, 8, 16, 4, 4, 16, 8)      # m = 8 = n
+    s = oracle.shape_of(c, own_is_candidate=True)
+    q, k, v = rand_qkv(c, 52)
+    full = oracle.select_all(s, q, k)
+    sc = oracle.scores(s, oracle.pool(s, q), oracle.pool(s, k))
+    for a in range(2):
+        for i in range(8):
+            order = np.lexsort((np.arange(8), -sc[0, a, i].astype(np.float64)))
+            assert np.array_equal(full[0, a, i], order)
+    # a shorter list is a prefix of the full ranking
+    s3 = oracle.shape_of(c, n_select=3, own_is_candidate=True)
+    assert np.array_equal(oracle.select_all(s3, q, k), full[..., :3])
+    # dropping the own block gives the ranking of the single-softmax form
+    s7 = oracle.shape_of(c, n_select=7)
+    others = oracle.select(s7, q, k)
+    for a in range(2):
+        for i in range(8):
+            assert np.array_equal(full[0, a, i][full[0, a, i] != i], others[0, a, i])
+    # a query block whose own key block scores highest selects itself first
+    assert (full[..., 0] == np.arange(8)).sum() < 16      # ... but not always: no special case
+
+
+def test_attend_lists_reduces_to_known_cases(oracle):
+    c = shape_ns(1, 2, 8, 12, 4, 4, 8, 2)       # m = 6
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 53, scale=1.3)
+    idx = random_selection(c, 54)
+    own = np.broadcast_to(np.arange(6, dtype=np.int32)[None, None, :, None], (1, 2, 6, 1))
+    # own block in front of the selection: the single-softmax forward
+    out, lse = oracle.attend_lists(s, q, k, v, np.concatenate([own, idx], axis=-1))
+    ref, ref_lse = oracle.fwd(s, q, k, v, idx)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(lse, ref_lse, rtol=0, atol=1e-13)
+    # every block listed (any order): dense attention
+    rng = np.random.default_rng(55)
+    everything = np.stack([rng.permutation(6) for _ in range(12)]).reshape(1, 2, 6, 6)
+    np.testing.assert_allclose(oracle.attend_lists(s, q, k, v, everything)[0], _sdpa(q, k, v),
+                               rtol=0, atol=1e-12)
+    # the selection alone: library attention over the gathered tiles, own block absent
+    out, _ = oracle.attend_lists(s, q, k, v, idx)
+    qt, kt, vt, ot = (to_tiles(x, c) for x in (q, k, v, out))
+    for a in range(2):
+        for i in range(6):
+            kk = np.concatenate([kt[0, a, j] for j in idx[0, a, i]])
+            vv = np.concatenate([vt[0, a, j] for j in idx[0, a, i]])
+            np.testing.assert_allclose(ot[0, a, i], _sdpa(qt[0, a, i], kk, vv), rtol=0, atol=1e-12)
+
+
+def test_local_branch_is_block_diagonal_attention_of_the_large_blocks(oracle):
+    c = shape_ns(1, 2, 8, 24, 2, 4, 8, 1)       # tiles 2 x 4, large blocks of 2 x 3 tiles
+    s = oracle.shape_of(c, own_is_candidate=True)
+    q, k, v = rand_qkv(c, 56)
+    win = oracle.local_lists(s, 2, 3)
+    assert win.shape == (c.n_blocks, 6)
+    for i in range(c.n_blocks):
+        assert i in win[i] and len(set(win[i])) == 6
+    out, _ = oracle.attend_lists(s, q, k, v, np.broadcast_to(win, (1, 2) + win.shape))
+    big = shape_ns(1, 2, 8, 24, 4, 12, 8, 0)    # the same large blocks as tiles of their own
+    ref = _sdpa(to_tiles(q, big), to_tiles(k, big), to_tiles(v, big))
+    np.testing.assert_allclose(to_tiles(out, big), ref, rtol=0, atol=1e-12)
+
+
+def test_three_branch_sum_follows_the_gates(oracle):
+    c = shape_ns(2, 4, 8, 16, 2, 4, 8, 3, kv_heads=2)     # grouped: 4 query heads on 2
+    s = oracle.shape_of(c, own_is_candidate=True)
+    q = rand_qkv(c, 57)[0]
+    k, v = _kv(c, 58, 2)
+    rng = np.random.default_rng(59)
+    gates = rng.uniform(0.0, 1.0, size=(2, 4, c.n_tokens, 3))
+    out, sel, (o_cg, o_fg, o_l) = oracle.fwd_three_branch(s, q, k, v, gates, 2, 2)
+    # one-hot gates isolate each branch
+    for br, o in enumerate((o_cg, o_fg, o_l)):
+        g1 = np.zeros_like(gates)
+        g1[..., br] = 1.0
+        np.testing.assert_array_equal(oracle.fwd_three_branch(s, q, k, v, g1, 2, 2)[0], o)
+    np.testing.assert_allclose(
+        out, gates[..., 0:1] * o_cg + gates[..., 1:2] * o_fg + gates[..., 2:3] * o_l,
+        rtol=0, atol=1e-14)
+    # the coarse output is constant inside a tile and differs between tiles
+    t = to_tiles(o_cg, c)
+    assert np.array_equal(t, np.broadcast_to(t[:, :, :, :1], t.shape))
+    assert np.abs(t[:, :, 0, 0] - t[:, :, 1, 0]).max() > 1e-3
+    # branches of query head a are those of the one-head problem on kv head a // 2
+    c1 = shape_ns(2, 1, 8, 16, 2, 4, 8, 3)
+    s1 = oracle.shape_of(c1, own_is_candidate=True)
+    for a in range(4):
+        u = a // 2
+        o1, sel1, _ = oracle.fwd_three_branch(s1, q[:, a:a + 1], k[:, u:u + 1], v[:, u:u + 1],
+                                              gates[:, a:a + 1], 2, 2)
+        assert np.array_equal(sel1, sel[:, a:a + 1])
+        np.testing.assert_array_equal(o1, out[:, a:a + 1])
+    # values that do not depend on the token come back scaled by the sum of the gates
+    vc = np.broadcast_to(rng.standard_normal((2, 2, 1, 8)).astype(np.float32), v.shape)
+    outc = oracle.fwd_three_branch(s, q, k, vc, gates, 2, 2)[0]
+    np.testing.assert_allclose(outc, gates.sum(-1, keepdims=True) * np.repeat(vc, 2, axis=1),
+                               rtol=0, atol=1e-6)
