@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="configuration id (1-5: the benchmark configurations; 6, 7: the paper's stage-1 shape, block-contiguous and tiled; 8, 9: configurations 3 and 6 with 4 query heads per key/value head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--three-branch", type=int, nargs=2, metavar=("LOCAL_H", "LOCAL_W"),
+                    help="also time the three-branch forward (coarse + selection + local "
+                         "branches, gated sum) with large local blocks of LOCAL_H x LOCAL_W tiles")
     ap.add_argument("--with-bwd", action="store_true",
                     help="also run the backward (selection held fixed) after the timed steps "
                          "and report its time; it is not part of a step")
@@ -190,6 +193,34 @@ def main():
         result["bwd_ms"] = bwd_ms
         # five block products per pair against the forward's two
         result["bwd_effective_tflops"] = 2.5 * flops / (bwd_ms * 1e-3) / 1e12
+    if args.three_branch:
+        lh, lw = args.three_branch
+        nbytes = M.mosaic_bsa_three_branch_workspace_bytes(prm, lh, lw)
+        if nbytes == 0:
+            sys.exit(f"--three-branch {lh} {lw}: the local group must divide the grid of tiles")
+        ws_t = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        gen = torch.Generator(device=dev).manual_seed(16429004)
+        gates = torch.rand((cfg.batch, cfg.heads, cfg.n_tokens, 3), generator=gen, device=dev,
+                           dtype=torch.float32)
+        out3 = torch.empty_like(q)
+        reps = max(2, args.steps // 2)
+        M.mosaic_bsa_fwd_three_branch(prm, lh, lw, q, k, v, gates, out3, idx, ws_t)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            M.mosaic_bsa_fwd_three_branch(prm, lh, lw, q, k, v, gates, out3, idx, ws_t)
+        e1.record()
+        torch.cuda.synchronize()
+        tb_ms = e0.elapsed_time(e1) / reps
+        # block products of the two attention branches: n selected blocks, and the
+        # lh*lw tiles of the large local block
+        tb_flops = flops // (cfg.n_select + 1) * (cfg.n_select + lh * lw)
+        result["three_branch"] = {
+            "local_group": [lh, lw], "ms": tb_ms,
+            "tokens_per_s": tokens / (tb_ms * 1e-3),
+            "effective_tflops": tb_flops / (tb_ms * 1e-3) / 1e12,
+        }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(problem, cfg)
     print(json.dumps(result))

@@ -56,7 +56,8 @@ enum {
     MOSAIC_BSA_ERR_NULL = -1,      /* a required pointer is NULL */
     MOSAIC_BSA_ERR_SHAPE = -2,     /* non-positive size, tile does not divide grid, or
                                       kv_heads does not divide heads */
-    MOSAIC_BSA_ERR_NSELECT = -3,   /* n_select < 0 or n_select > m - 1 */
+    MOSAIC_BSA_ERR_NSELECT = -3,   /* n_select outside [0, m - 1] ([1, m] in the
+                                      three-branch form) */
     MOSAIC_BSA_ERR_HEAD_DIM = -4,  /* head_dim not in {32, 64, 128} */
     MOSAIC_BSA_ERR_DTYPE = -5,     /* dtype not MOSAIC_BSA_F32 / MOSAIC_BSA_BF16 */
     MOSAIC_BSA_ERR_WORKSPACE = -6, /* workspace missing or too small */
@@ -148,6 +149,50 @@ int mosaic_bsa_bwd(const mosaic_bsa_params *params, const void *q, const void *k
                    const void *v, const void *out, const float *lse, const void *dout,
                    const int32_t *sel_idx, void *dq, void *dk, void *dv,
                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The paper's three-branch output (Block-Sparse Attention subsection:
+ * Compression, Selection and Local Attention paragraphs; gated sum of the
+ * aggregation equation in the Native Sparse Attention subsection):
+ *
+ *   o_l = g_cg(l) * o_cg(l) + g_fg(l) * o_fg(l) + g_loc(l) * o_loc(l)
+ *
+ *   coarse     o_cg(l) = sum_j abar_ij vbar_j for every token l of block i,
+ *              abar_i = softmax over ALL m blocks of qbar_i . kbar_j * scale,
+ *              vbar_j the mean-pooled values;
+ *   selection  S_i = the n largest entries of row i over all m blocks (the
+ *              block itself is a candidate; 1 <= n_select <= m; ranked by the
+ *              pinned fp32 pooled dot product, ties to the smaller index);
+ *              o_fg = one softmax over the tokens of the blocks in S_i only;
+ *   local      one softmax over the tokens of the large block that contains
+ *              l: the aligned group of local_h x local_w mesh tiles
+ *              (local_h divides grid_h / block_h, local_w divides
+ *              grid_w / block_w; 1 x 1 = the tile itself);
+ *   gates      caller-supplied values, one per token, head and branch.
+ *
+ *   q             in   device, [B, heads, N, D]
+ *   k, v          in   device, [B, kv_heads, N, D]
+ *   gates         in   device, fp32 [B, heads, N, 3] in the order (coarse,
+ *                      selection, local)
+ *   out           out  device, [B, heads, N, D], element type of q
+ *   sel_idx       out  device, int32 [B, heads, m, n]: S_i in ranking order
+ *   workspace          device scratch of
+ *                      mosaic_bsa_three_branch_workspace_bytes(..) bytes (pooled
+ *                      tensors, block lists and the two attention branches'
+ *                      outputs in the element type of q); contents undefined
+ *                      on return.
+ * The branch outputs are rounded to the element type of q before the gated
+ * sum, which runs in fp32.  Errors as for the other entry points; a local
+ * group that does not divide the grid of tiles is MOSAIC_BSA_ERR_SHAPE.
+ * mosaic_bsa_three_branch_workspace_bytes returns 0 for invalid arguments.
+ */
+size_t mosaic_bsa_three_branch_workspace_bytes(const mosaic_bsa_params *params,
+                                               int32_t local_h, int32_t local_w);
+int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params *params, int32_t local_h,
+                                int32_t local_w, const void *q, const void *k,
+                                const void *v, const float *gates, void *out,
+                                int32_t *sel_idx, void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
 
 /* Static, human-readable text for a return code. */
 const char *mosaic_bsa_strerror(int code);

@@ -90,6 +90,11 @@ def load_library() -> ctypes.CDLL:
         lib.mosaic_bsa_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.mosaic_bsa_bwd.restype = i32
         lib.mosaic_bsa_bwd.argtypes = [pp] + [vp] * 10 + [vp, sz, vp]
+        lib.mosaic_bsa_three_branch_workspace_bytes.restype = sz
+        lib.mosaic_bsa_three_branch_workspace_bytes.argtypes = [pp, ctypes.c_int32, ctypes.c_int32]
+        lib.mosaic_bsa_fwd_three_branch.restype = i32
+        lib.mosaic_bsa_fwd_three_branch.argtypes = (
+            [pp, ctypes.c_int32, ctypes.c_int32] + [vp] * 7 + [sz, vp])
         lib.mosaic_bsa_strerror.restype = ctypes.c_char_p
         lib.mosaic_bsa_strerror.argtypes = [i32]
         _lib = lib
@@ -160,3 +165,19 @@ def mosaic_bsa_bwd(params: Params, q, k, v, out, lse, dout, sel_idx, dq, dk, dv,
         ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
         _ptr(dout), _ptr(sel_idx), _ptr(dq), _ptr(dk), _ptr(dv),
         _ptr(workspace), wb, _stream(stream)))
+
+
+def mosaic_bsa_three_branch_workspace_bytes(params: Params, local_h: int, local_w: int) -> int:
+    cp = params.c_struct()
+    return int(load_library().mosaic_bsa_three_branch_workspace_bytes(
+        ctypes.byref(cp), int(local_h), int(local_w)))
+
+
+def mosaic_bsa_fwd_three_branch(params: Params, local_h: int, local_w: int, q, k, v, gates,
+                                out, sel_idx, workspace, stream=None,
+                                workspace_bytes=None) -> None:
+    cp = params.c_struct()
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(load_library().mosaic_bsa_fwd_three_branch(
+        ctypes.byref(cp), int(local_h), int(local_w), _ptr(q), _ptr(k), _ptr(v), _ptr(gates),
+        _ptr(out), _ptr(sel_idx), _ptr(workspace), wb, _stream(stream)))

@@ -17,7 +17,9 @@ struct Checked {
     bool is_bf16;
 };
 
-int check_params(const mosaic_bsa_params* p, Checked* out)
+// own_is_candidate: the three-branch form, where the top-n runs over all m
+// blocks (1 <= n <= m); otherwise 0 <= n <= m - 1.
+int check_params(const mosaic_bsa_params* p, Checked* out, bool own_is_candidate = false)
 {
     if (!p) return MOSAIC_BSA_ERR_NULL;
     if (p->batch <= 0 || p->heads <= 0 || p->grid_h <= 0 || p->grid_w <= 0 || p->block_h <= 0 ||
@@ -35,7 +37,9 @@ int check_params(const mosaic_bsa_params* p, Checked* out)
     if (p->head_dim != 32 && p->head_dim != 64 && p->head_dim != 128)
         return MOSAIC_BSA_ERR_HEAD_DIM;
     if (p->dtype != MOSAIC_BSA_F32 && p->dtype != MOSAIC_BSA_BF16) return MOSAIC_BSA_ERR_DTYPE;
-    if (p->n_select < 0 || p->n_select > m - 1) return MOSAIC_BSA_ERR_NSELECT;
+    if (own_is_candidate ? (p->n_select < 1 || p->n_select > m)
+                         : (p->n_select < 0 || p->n_select > m - 1))
+        return MOSAIC_BSA_ERR_NSELECT;
     const int kv_heads = p->kv_heads == 0 ? p->heads : p->kv_heads;
     if (kv_heads < 0 || kv_heads > p->heads || p->heads % kv_heads) return MOSAIC_BSA_ERR_SHAPE;
 
@@ -55,6 +59,8 @@ int check_params(const mosaic_bsa_params* p, Checked* out)
     g.n_tokens = N;
     g.scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
     g.kv_group = p->heads / kv_heads;
+    g.list_only = 0;
+    g.own_is_candidate = own_is_candidate ? 1 : 0;
     return MOSAIC_BSA_OK;
 }
 
@@ -110,6 +116,23 @@ extern "C" int mosaic_bsa_select(const mosaic_bsa_params* params, const void* q,
     return MOSAIC_BSA_OK;
 }
 
+namespace {
+
+// The attention forward for geometry g (which may differ from the checked one
+// in its block lists): matrix-core kernels where they apply.
+hipError_t forward(const Checked& c, const bsa::Geom& g, const void* q, const void* k,
+                   const void* v, const int32_t* lists, void* out, float* lse,
+                   hipStream_t stream)
+{
+    if (bsa::fwd_mfma_supported(c.is_bf16, g, c.D))
+        return bsa::launch_fwd_mfma(q, k, v, lists, out, lse, g, c.D, c.BH, stream);
+    if (bsa::fwd_mfma_d128_supported(c.is_bf16, g, c.D))
+        return bsa::launch_fwd_mfma_d128(q, k, v, lists, out, lse, g, c.BH, stream);
+    return bsa::launch_fwd_generic(c.is_bf16, q, k, v, lists, out, lse, g, c.D, c.BH, stream);
+}
+
+}  // namespace
+
 extern "C" int mosaic_bsa_fwd(const mosaic_bsa_params* params, const void* q, const void* k,
                               const void* v, const int32_t* sel_idx, void* out, float* lse,
                               void* workspace, size_t workspace_bytes, void* hip_stream)
@@ -123,16 +146,110 @@ extern "C" int mosaic_bsa_fwd(const mosaic_bsa_params* params, const void* q, co
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
         return MOSAIC_BSA_ERR_ALIGN;
 
+    return forward(c, c.g, q, k, v, sel_idx, out, lse, (hipStream_t)hip_stream) == hipSuccess
+               ? MOSAIC_BSA_OK
+               : MOSAIC_BSA_ERR_LAUNCH;
+}
+
+namespace {
+
+// Workspace of the three-branch forward: 256-byte aligned parts in this order.
+struct ThreeBranchLayout {
+    size_t qbar, kbar, vbar, obar, lists, o_fg, o_l, total;
+};
+
+ThreeBranchLayout three_branch_layout(const Checked& c, int local_tiles)
+{
+    const size_t m = (size_t)c.g.n_blocks, esz = c.is_bf16 ? 2 : 4;
+    ThreeBranchLayout w;
+    size_t at = 0;
+    auto take = [&](size_t bytes) {
+        const size_t start = at;
+        at += align_up(bytes);
+        return start;
+    };
+    w.qbar = take((size_t)c.BH * m * c.D * 4);
+    w.kbar = take((size_t)c.BKV * m * c.D * 4);
+    w.vbar = take((size_t)c.BKV * m * c.D * 4);
+    w.obar = take((size_t)c.BH * m * c.D * 4);
+    w.lists = take((size_t)c.BH * m * (size_t)(local_tiles - 1) * 4);
+    w.o_fg = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
+    w.o_l = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
+    w.total = at;
+    return w;
+}
+
+int check_local(const mosaic_bsa_params* p, int local_h, int local_w)
+{
+    if (local_h <= 0 || local_w <= 0) return MOSAIC_BSA_ERR_SHAPE;
+    if ((p->grid_h / p->block_h) % local_h || (p->grid_w / p->block_w) % local_w)
+        return MOSAIC_BSA_ERR_SHAPE;
+    return MOSAIC_BSA_OK;
+}
+
+}  // namespace
+
+extern "C" size_t mosaic_bsa_three_branch_workspace_bytes(const mosaic_bsa_params* params,
+                                                          int32_t local_h, int32_t local_w)
+{
+    Checked c;
+    if (check_params(params, &c, true) || check_local(params, local_h, local_w)) return 0;
+    if (bsa::select_group_size(c.g.n_blocks, c.D) == 0) return 0;
+    return three_branch_layout(c, local_h * local_w).total;
+}
+
+extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int32_t local_h,
+                                           int32_t local_w, const void* q, const void* k,
+                                           const void* v, const float* gates, void* out,
+                                           int32_t* sel_idx, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream)
+{
+    Checked c;
+    if (int rc = check_params(params, &c, true)) return rc;
+    if (int rc = check_local(params, local_h, local_w)) return rc;
+    if (!q || !k || !v || !gates || !out || !sel_idx) return MOSAIC_BSA_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) ||
+        misaligned(workspace))
+        return MOSAIC_BSA_ERR_ALIGN;
+    if (bsa::select_group_size(c.g.n_blocks, c.D) == 0) return MOSAIC_BSA_ERR_SHAPE;
+    const int local_tiles = local_h * local_w;
+    const ThreeBranchLayout w = three_branch_layout(c, local_tiles);
+    if (!workspace || workspace_bytes < w.total) return MOSAIC_BSA_ERR_WORKSPACE;
+
     hipStream_t stream = (hipStream_t)hip_stream;
-    hipError_t e;
-    if (bsa::fwd_mfma_supported(c.is_bf16, c.g, c.D))
-        e = bsa::launch_fwd_mfma(q, k, v, sel_idx, out, lse, c.g, c.D, c.BH, stream);
-    else if (bsa::fwd_mfma_d128_supported(c.is_bf16, c.g, c.D))
-        e = bsa::launch_fwd_mfma_d128(q, k, v, sel_idx, out, lse, c.g, c.BH, stream);
-    else
-        e = bsa::launch_fwd_generic(c.is_bf16, q, k, v, sel_idx, out, lse, c.g, c.D, c.BH,
-                                    stream);
-    return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
+    char* ws = (char*)workspace;
+    float* qbar = (float*)(ws + w.qbar);
+    float* kbar = (float*)(ws + w.kbar);
+    float* vbar = (float*)(ws + w.vbar);
+    float* obar = (float*)(ws + w.obar);
+    int32_t* lists = (int32_t*)(ws + w.lists);
+    void* o_fg = ws + w.o_fg;
+    void* o_l = ws + w.o_l;
+
+    // compression: pooled q, k, v
+    if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess ||
+        bsa::launch_pool_one(c.is_bf16, v, vbar, c.g, c.D, c.BKV, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // coarse branch, and the ranking it shares with the selection branch
+    if (bsa::launch_coarse(qbar, kbar, vbar, obar, c.g, c.D, c.BH, stream) != hipSuccess ||
+        bsa::launch_select(qbar, kbar, sel_idx, c.g, c.D, c.BH, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // selection branch: one softmax over the selected blocks only
+    bsa::Geom g_fg = c.g;
+    g_fg.list_only = 1;
+    if (forward(c, g_fg, q, k, v, sel_idx, o_fg, nullptr, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // local branch: the tile and the other tiles of its large block
+    bsa::Geom g_l = c.g;
+    g_l.n_select = local_tiles - 1;
+    if (bsa::launch_local_lists(lists, c.g, local_h, local_w, c.BH, stream) != hipSuccess ||
+        forward(c, g_l, q, k, v, lists, o_l, nullptr, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // gated sum
+    if (bsa::launch_combine(c.is_bf16, obar, o_fg, o_l, gates, out, c.g, c.D, c.BH, stream) !=
+        hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    return MOSAIC_BSA_OK;
 }
 
 extern "C" int mosaic_bsa_bwd(const mosaic_bsa_params* params, const void* q, const void* k,
@@ -169,7 +286,9 @@ extern "C" const char* mosaic_bsa_strerror(int code)
     case MOSAIC_BSA_ERR_SHAPE:
         return "invalid shape: sizes must be positive, the tile must divide the grid, "
                "b <= 1024 and the problem must fit the launch limits";
-    case MOSAIC_BSA_ERR_NSELECT: return "n_select must satisfy 0 <= n_select <= m - 1";
+    case MOSAIC_BSA_ERR_NSELECT:
+        return "n_select must satisfy 0 <= n_select <= m - 1 (1 <= n_select <= m in the "
+               "three-branch form)";
     case MOSAIC_BSA_ERR_HEAD_DIM: return "head_dim must be 32, 64 or 128";
     case MOSAIC_BSA_ERR_DTYPE: return "dtype must be MOSAIC_BSA_F32 or MOSAIC_BSA_BF16";
     case MOSAIC_BSA_ERR_WORKSPACE: return "workspace is NULL or smaller than required";

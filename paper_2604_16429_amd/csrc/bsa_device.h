@@ -21,6 +21,9 @@ struct Geom {
     int64_t n_tokens;     // N
     float   scale;        // softmax scale
     int32_t kv_group;     // query heads per key/value head (1 = every head has its own)
+    int32_t list_only;    // forward: 1 = attend exactly the n listed blocks (n >= 1), 0 = block i
+                          // itself, then the n listed blocks
+    int32_t own_is_candidate;  // selection: 1 = rank all m key blocks, 0 = all but block i
 };
 
 // [N, D] slice of K and V that the query slice bh = batch * heads + head

@@ -32,13 +32,18 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(
     const int64_t blk = blockIdx.x / row_chunks;
     const int i = (int)(blk % g.n_blocks);
     const int64_t bh_idx = blk / g.n_blocks;
-    const int b = g.block_tokens, n = g.n_select;
+    const int b = g.block_tokens;
     const int tau_q = rc * 64 + threadIdx.x;
     const bool valid = tau_q < b;
     const int64_t base = bh_idx * g.n_tokens * D;
     const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
     const int64_t tok_q = token_of(g, i, valid ? tau_q : 0);
-    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
+    // The attended blocks: block i itself followed by its selected blocks, or,
+    // when the selection branch runs on its own, exactly the listed blocks.
+    const int list_only = g.list_only;
+    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * g.n_select + list_only;
+    const int first = list_only ? sel_row[-1] : i;
+    const int n = g.n_select - list_only;        // blocks after the first
     const float scale2 = g.scale * 1.4426950408889634f;   // to base-2 exponent
 
     float qr[D], acc[D];
@@ -52,7 +57,7 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(
     float m_run = -INFINITY, l_run = 0.0f;
 
     for (int c = 0; c <= n; ++c) {
-        const int beta = (c == 0) ? i : sel_row[c - 1];
+        const int beta = (c == 0) ? first : sel_row[c - 1];
         for (int k0 = 0; k0 < b; k0 += KC) {
             const int kcnt = min(KC, b - k0);
             __syncthreads();

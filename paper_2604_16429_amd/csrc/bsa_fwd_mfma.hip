@@ -221,7 +221,6 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     const int lane = threadIdx.x & 63;
     const int wave = NW == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int n = g.n_select;
 
     // Work item -> (query slice, query block); key/value slices are dealt to
     // the XCDs whole (map_workgroup).  A work item is NW consecutive
@@ -238,7 +237,12 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     }
     const int64_t base = bh_idx * g.n_tokens * D;
     const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
-    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
+    // The attended blocks: block i itself followed by its selected blocks, or,
+    // when the selection branch runs on its own, exactly the listed blocks.
+    const int list_only = g.list_only;
+    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * g.n_select + list_only;
+    const int first = list_only ? sel_row[-1] : i;
+    const int n = g.n_select - list_only;        // blocks after the first
     q += base; out += base;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
     const __amdgpu_buffer_rsrc_t k_rsrc =
@@ -257,9 +261,9 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     // rounding).  The order is computed after the first gathers are in flight;
     // order_v: lane c holds the c-th block to visit.
     const bool sorted = n + 1 <= 64;
-    int order_v = i;
+    int order_v = first;
     auto block_at = [&](int c) -> int {
-        if (c == 0) return i;
+        if (c == 0) return first;
         if (__builtin_expect(sorted, 1)) return __builtin_amdgcn_readlane(order_v, c);
         return sel_row[c - 1];
     };
@@ -281,7 +285,7 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
 
     // K(0) and V(0) go to LDS
     {
-        const uint32_t origin_0 = origin_of(i) + (uint32_t)0;
+        const uint32_t origin_0 = origin_of(first) + (uint32_t)0;
         // (split between the wavefronts of the workgroup: slab r belongs to
         // wavefront r mod NW)
 #define BSA_GATHER_MINE(R, RSRC, ORIGIN, LDS) \

@@ -84,7 +84,6 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int n = g.n_select;
     const int subs = g.block_tokens / 64;          // 64-key sub-tiles per attended block
 
     // Workgroup -> (query slice, query block); key/value slices are dealt to
@@ -94,7 +93,12 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     map_workgroup(g, blockIdx.x, (uint32_t)g.n_blocks, n_units, bh_idx, i);
     const int64_t base = bh_idx * g.n_tokens * D;
     const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
-    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
+    // The attended blocks: block i itself followed by its selected blocks, or,
+    // when the selection branch runs on its own, exactly the listed blocks.
+    const int list_only = g.list_only;
+    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * g.n_select + list_only;
+    const int first = list_only ? sel_row[-1] : i;
+    const int n = g.n_select - list_only;        // blocks after the first
     q += base; out += base;
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
     const __amdgpu_buffer_rsrc_t k_rsrc =
@@ -110,9 +114,9 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     // an XCD then sweep the slice's K/V in the same direction).  Every
     // wavefront computes the order for itself; lane c holds the c-th block.
     const bool sorted = n + 1 <= 64;
-    int order_v = i;
+    int order_v = first;
     auto block_at = [&](int c) -> int {
-        if (c == 0) return i;
+        if (c == 0) return first;
         if (__builtin_expect(sorted, 1)) return __builtin_amdgcn_readlane(order_v, c);
         return sel_row[c - 1];
     };
@@ -151,7 +155,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
 
     // pair 0: K (both halves) and the lower half of V go to LDS
     {
-        const uint32_t origin_0 = origin_of(i);
+        const uint32_t origin_0 = origin_of(first);
         refill_half(k_rsrc, origin_0, 0, k_lds0);
         refill_half(k_rsrc, origin_0, 1, k_lds1);
         refill_half(v_rsrc, origin_0, 0, v_lds0);
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         if (++pct == subs) { pct = 0; ++pcb; }
         return origin_of(block_at(pcb <= n ? pcb : n)) + (uint32_t)(sub_tile_first(g, pct) * ROW_BYTES);
     };
-    uint32_t o0 = origin_of(i);                        // origin of pair c
+    uint32_t o0 = origin_of(first);                        // origin of pair c
     uint32_t o1 = next_origin();                       // origin of pair c + 1
 
     // ---- pipeline prologue

@@ -15,6 +15,10 @@ int select_group_size(int m, int D);
 hipError_t launch_pool(bool is_bf16, const void* q, const void* k, float* qbar, float* kbar,
                        const Geom& g, int D, int64_t BH, hipStream_t stream);
 
+// Pooled means of one key/value-shaped tensor (slices = batch * kv_heads).
+hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom& g, int D,
+                           int64_t slices, hipStream_t stream);
+
 hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, const Geom& g,
                          int D, int64_t BH, hipStream_t stream);
 
@@ -49,5 +53,17 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
                            const float* lse, const void* dout, const int32_t* sel_idx, void* dq,
                            void* dk, void* dv, float* delta, float* lse2, const Geom& g, int D,
                            int64_t BH, hipStream_t stream);
+
+// Three-branch output: coarse branch (softmax over all pooled key blocks times
+// pooled values, fp32 [B*heads, m, D]), the block lists of the local branch
+// (int32 [B*heads, m, local_h*local_w - 1]) and the gated sum of the branches.
+int coarse_group_size(int m, int D);
+hipError_t launch_coarse(const float* qbar, const float* kbar, const float* vbar, float* obar,
+                         const Geom& g, int D, int64_t BH, hipStream_t stream);
+hipError_t launch_local_lists(int32_t* lists, const Geom& g, int local_h, int local_w,
+                              int64_t BH, hipStream_t stream);
+hipError_t launch_combine(bool is_bf16, const float* obar, const void* o_fg, const void* o_l,
+                          const float* gates, void* out, const Geom& g, int D, int64_t BH,
+                          hipStream_t stream);
 
 }  // namespace bsa

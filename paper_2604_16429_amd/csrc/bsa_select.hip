@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
                 acc = __builtin_fmaf(qv.z, kr[4 * d4 + 2], acc);
                 acc = __builtin_fmaf(qv.w, kr[4 * d4 + 3], acc);
             }
-            key_s[r * m + j] = (j == i0 + r) ? 0u : rank_key(acc);
+            key_s[r * m + j] = (j == i0 + r && !g.own_is_candidate) ? 0u : rank_key(acc);
         }
     }
     __syncthreads();
@@ -278,6 +278,24 @@ hipError_t launch_pool(bool is_bf16, const void* q, const void* k, float* qbar, 
 {
     return is_bf16 ? launch_pool_t<uint16_t, 8>(q, k, qbar, kbar, g, D, BH, stream)
                    : launch_pool_t<float, 4>(q, k, qbar, kbar, g, D, BH, stream);
+}
+
+hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom& g, int D,
+                           int64_t slices, hipStream_t stream)
+{
+    // the pooling kernel with no query slices: every slice is a "key" slice
+    const int items = g.n_blocks * (D / (is_bf16 ? 8 : 4));
+    const int wgs_per_slice = (items + 255) / 256;
+    dim3 grid((unsigned)(slices * wgs_per_slice));
+    if (is_bf16)
+        hipLaunchKernelGGL((pool_kernel<uint16_t, 8>), grid, dim3(256), 0, stream,
+                           (const uint16_t*)nullptr, (const uint16_t*)x, (float*)nullptr, xbar, g,
+                           D, (int64_t)0, wgs_per_slice);
+    else
+        hipLaunchKernelGGL((pool_kernel<float, 4>), grid, dim3(256), 0, stream,
+                           (const float*)nullptr, (const float*)x, (float*)nullptr, xbar, g, D,
+                           (int64_t)0, wgs_per_slice);
+    return hipGetLastError();
 }
 
 template <int D>

@@ -69,3 +69,19 @@ def gpu_bwd(cfg, q, k, v, dout, idx, n_select=None, softmax_scale=0.0):
     M.mosaic_bsa_bwd(p, q_d, k_d, v_d, out, lse, do_d, idx_d, dq, dk, dv, ws)
     torch.cuda.synchronize()
     return tuple(t.float().cpu().numpy() for t in (dq, dk, dv))
+
+
+def gpu_fwd_three_branch(cfg, q, k, v, gates, local_h, local_w, softmax_scale=0.0):
+    """Three-branch forward on the GPU; returns (out fp32 numpy, sel_idx)."""
+    p = params_of(cfg, None, softmax_scale)
+    q_d, k_d, v_d = (to_dev(x, cfg) for x in (q, k, v))
+    g_d = torch.from_numpy(np.ascontiguousarray(gates, dtype=np.float32)).to("cuda")
+    out = torch.full_like(q_d, float("nan"))
+    idx = torch.full((cfg.batch, cfg.heads, p.n_blocks, p.n_select), -1, dtype=torch.int32,
+                     device="cuda")
+    nbytes = M.mosaic_bsa_three_branch_workspace_bytes(p, local_h, local_w)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    M.mosaic_bsa_fwd_three_branch(p, local_h, local_w, q_d, k_d, v_d, g_d, out, idx, ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), idx.cpu().numpy()

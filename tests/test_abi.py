@@ -26,7 +26,9 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(mosaic_bsa_[a-z_]+)\s*\(", header))
     assert {"mosaic_bsa_select", "mosaic_bsa_fwd", "mosaic_bsa_bwd",
-            "mosaic_bsa_workspace_bytes", "mosaic_bsa_strerror"} <= names
+            "mosaic_bsa_workspace_bytes", "mosaic_bsa_strerror",
+            "mosaic_bsa_fwd_three_branch",
+            "mosaic_bsa_three_branch_workspace_bytes"} <= names
     for name in names:
         assert hasattr(lib, name), name
     # the Python binding carries the same names
@@ -111,3 +113,31 @@ def test_strerror_covers_all_codes():
     texts = {M.mosaic_bsa_strerror(c) for c in range(0, -10, -1)}
     assert len(texts) == 10 and "unknown error code" not in texts
     assert M.mosaic_bsa_strerror(-99) == "unknown error code"
+
+
+def test_three_branch_arguments_are_checked_on_the_host():
+    p = good(n_select=32)        # n = m is allowed here: the own block is a candidate
+    fake = 0x1000
+    m, N, D = 32, 2048, 32
+
+    def part(nbytes):
+        return (nbytes + 255) // 256 * 256
+    expect = (4 * part(2 * m * D * 4) + part(2 * m * 3 * 4) + 2 * part(2 * N * D * 4))
+    assert M.mosaic_bsa_three_branch_workspace_bytes(p, 2, 2) == expect
+    assert M.mosaic_bsa_three_branch_workspace_bytes(p, 3, 2) == 0      # 4 x 8 tiles
+    assert M.mosaic_bsa_three_branch_workspace_bytes(good(n_select=0), 1, 1) == 0
+    args = [fake] * 7
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_fwd_three_branch(good(n_select=33), 1, 1, *args, stream=0,
+                                      workspace_bytes=1 << 30)
+    assert e.value.code == -3
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_fwd_three_branch(p, 2, 3, *args, stream=0, workspace_bytes=1 << 30)
+    assert e.value.code == -2
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_fwd_three_branch(p, 2, 2, fake, fake, fake, None, fake, fake, fake,
+                                      stream=0, workspace_bytes=1 << 30)
+    assert e.value.code == -1
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_fwd_three_branch(p, 2, 2, *args, stream=0, workspace_bytes=expect - 1)
+    assert e.value.code == -6

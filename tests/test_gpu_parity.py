@@ -372,3 +372,51 @@ def test_grouped_query_attention(G, oracle, dtype, B, heads, kv_heads, H, W, bh,
     got = G.gpu_bwd(cfg, q, k, v, dout, idx_ref)
     assert got[1].shape == k.shape and got[2].shape == v.shape
     check_grads(cfg, got, ref)
+
+
+# --------------------------------------------------------------------------
+# the three branches with their own softmaxes and the gated sum
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,B,heads,kv_heads,H,W,bh,bw,D,n,lh,lw", [
+    ("fp32", 1, 2, 0, 32, 64, 8, 8, 32, 4, 2, 2),     # general kernels
+    ("fp32", 2, 4, 2, 12, 18, 6, 6, 32, 6, 1, 3),     # n = m, b = 36, grouped heads
+    ("bf16", 2, 4, 0, 32, 64, 8, 8, 64, 4, 2, 4),     # head dim 64 matrix-core kernels
+    ("bf16", 1, 4, 1, 32, 64, 8, 8, 64, 1, 1, 1),     # n = 1, local block = the tile itself
+    ("bf16", 1, 8, 2, 16, 256, 1, 128, 64, 5, 2, 2),  # block-contiguous 128-token blocks, grouped
+    ("bf16", 2, 2, 0, 32, 64, 8, 16, 128, 3, 2, 2),   # head dim 128 matrix-core kernel
+    ("bf16", 1, 2, 0, 120, 240, 8, 8, 64, 16, 3, 5),  # the 1.5 degree grid, m = 450
+])
+def test_three_branch_forward(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n, lh, lw):
+    cfg = shape_ns(B, heads, H, W, bh, bw, D, n, dtype, kv_heads=kv_heads)
+    hk = kv_heads or heads
+    rng = np.random.default_rng(8000 + H + D + n)
+    q = rng.standard_normal((B, heads, H * W, D)).astype(np.float32)
+    k, v = (rng.standard_normal((B, hk, H * W, D)).astype(np.float32) for _ in range(2))
+    if dtype == "bf16":
+        q, k, v = (round_to_bf16(x) for x in (q, k, v))
+    gates = rng.uniform(0.0, 1.0, size=(B, heads, H * W, 3)).astype(np.float32)
+    s = oracle.shape_of(cfg, own_is_candidate=True)
+    ref, sel_ref, _ = oracle.fwd_three_branch(s, q, k, v, gates, lh, lw)
+    got, sel = G.gpu_fwd_three_branch(cfg, q, k, v, gates, lh, lw)
+    assert np.array_equal(sel, sel_ref)
+    if dtype == "bf16":
+        err = np.abs(got - ref).max()
+        assert err <= 2e-2, f"bf16 max-abs error {err}"
+    else:
+        rel = np.abs(got - ref).max() / np.abs(ref).max()
+        assert rel <= 1e-5, f"fp32 relative error {rel}"
+
+
+def test_three_branch_gates_isolate_the_branches(G, oracle):
+    """One-hot gates: each branch on its own against the oracle's branch."""
+    cfg = shape_ns(1, 2, 32, 64, 8, 8, 64, 3, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 77))
+    s = oracle.shape_of(cfg, own_is_candidate=True)
+    ones = np.ones((1, 2, cfg.n_tokens, 3), dtype=np.float32)
+    _, _, branches = oracle.fwd_three_branch(s, q, k, v, ones, 2, 2)
+    for br in range(3):
+        gates = np.zeros_like(ones)
+        gates[..., br] = 1.0
+        got, _ = G.gpu_fwd_three_branch(cfg, q, k, v, gates, 2, 2)
+        err = np.abs(got - branches[br]).max()
+        assert err <= 2e-2, f"branch {br}: max-abs error {err}"
