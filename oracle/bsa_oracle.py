@@ -166,15 +166,24 @@ def fwd_blocks(s, q, k, v, sel_idx, pairs, scale: float = 0.0):
 
     Returns (out [cnt, b, D], lse [cnt, b]) float64 with rows in in-tile order.
     Works slice by slice on views of the inputs (no copies of the tensors).
+    k, v may carry fewer heads than q (grouped query attention: query head a
+    reads head a // group).
     """
     B, h, N, D, b, m = _dims(s)
     q, _ = _f32(q)
     k, _ = _f32(k)
     v, _ = _f32(v)
-    _check(s, q, k, v)
+    _check(s, q)
+    kv_heads = k.shape[1]
+    assert k.shape == v.shape == (B, kv_heads, N, D) and h % kv_heads == 0
     sel_idx, _ = _i32(sel_idx)
     pairs = np.ascontiguousarray(pairs, dtype=np.int64).reshape(-1, 2)
-    q3, k3, v3 = (x.reshape(B * h, N, D) for x in (q, k, v))
+    q3 = q.reshape(B * h, N, D)
+    k3, v3 = (x.reshape(B * kv_heads, N, D) for x in (k, v))
+
+    def kv_slice(g):
+        e, a = divmod(int(g), h)
+        return e * kv_heads + a // (h // kv_heads)
     i3 = sel_idx.reshape(B * h, m, s.n_select)
     sub = _shape(1, 1, s.grid_h, s.grid_w, s.block_h, s.block_w, D, s.n_select)
     out = np.empty((len(pairs), b, D), dtype=np.float64)
@@ -187,7 +196,8 @@ def fwd_blocks(s, q, k, v, sel_idx, pairs, scale: float = 0.0):
         p_s = np.ascontiguousarray(np.stack([np.zeros_like(blocks), blocks], axis=1))
         _load().oracle_fwd_blocks(
             ctypes.byref(sub), q3[g].ctypes.data_as(ctypes.c_void_p),
-            k3[g].ctypes.data_as(ctypes.c_void_p), v3[g].ctypes.data_as(ctypes.c_void_p),
+            k3[kv_slice(g)].ctypes.data_as(ctypes.c_void_p),
+            v3[kv_slice(g)].ctypes.data_as(ctypes.c_void_p),
             i3[g].ctypes.data_as(ctypes.c_void_p), ctypes.c_double(scale),
             p_s.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(len(p_s)),
             full_o.ctypes.data_as(ctypes.c_void_p), full_l.ctypes.data_as(ctypes.c_void_p))

@@ -224,7 +224,7 @@ def full_size_check(G, oracle, p, pairs):
     out_d, lse_d = G.fwd_dev(cfg, q_d, k_d, v_d, idx_d)
     torch.cuda.synchronize()
     idx = idx_d.cpu().numpy()
-    assert np.array_equal(idx, oracle.select(s, p.q, p.k))
+    assert np.array_equal(idx, oracle.select_gqa(s, p.q, p.k))
     out_ref, lse_ref = oracle.fwd_blocks(s, p.q, p.k, p.v, idx, pairs)
     bh = cfg.batch * cfg.heads
     out_t = out_d.view(bh, cfg.n_tokens, cfg.head_dim)
@@ -266,6 +266,26 @@ def test_config5_full_size_forward_sampled(G, oracle):
     rng = np.random.default_rng(55)
     pairs = [[int(g), int(i)] for g in rng.choice(cfg.batch * cfg.heads, size=8, replace=False)
              for i in rng.choice(cfg.n_blocks, size=4, replace=False)]
+    full_size_check(G, oracle, p, np.array(pairs))
+
+
+def test_config8_grouped_heads_full_size_sampled(G, oracle):
+    """Configuration 3's shape with 4 query heads per key/value head."""
+    p = make_problem(8)
+    cfg = p.cfg
+    rng = np.random.default_rng(88)
+    pairs = [[int(g), int(i)] for g in rng.choice(cfg.batch * cfg.heads, size=24, replace=False)
+             for i in rng.choice(cfg.n_blocks, size=12, replace=False)]
+    full_size_check(G, oracle, p, np.array(pairs))
+
+
+def test_config9_paper_stage1_shape_full_size_sampled(G, oracle):
+    """49,152 tokens as 384 contiguous blocks of 128, 24 selected, grouped heads."""
+    p = make_problem(9)
+    cfg = p.cfg
+    rng = np.random.default_rng(99)
+    pairs = [[int(g), int(i)] for g in rng.choice(cfg.batch * cfg.heads, size=12, replace=False)
+             for i in rng.choice(cfg.n_blocks, size=6, replace=False)]
     full_size_check(G, oracle, p, np.array(pairs))
 
 

@@ -457,6 +457,13 @@ def test_gqa_head_by_head_equals_single_head_problems(oracle):
     np.testing.assert_allclose(dv, dv_sum, rtol=0, atol=1e-13)
     # the two query heads of a group see the same keys but select differently
     assert not np.array_equal(idx[:, 0], idx[:, 1])
+    # the sampled forward reads the shared heads in place
+    pairs = np.array([[0, 3], [1, 0], [2, 11], [3, 7]])
+    o_s, l_s = oracle.fwd_blocks(s, q, k, v, idx, pairs)
+    ot, lt = to_tiles(out, c), to_tiles(lse[..., None], c)[..., 0]
+    for w, (g, i) in enumerate(pairs):
+        np.testing.assert_array_equal(o_s[w], ot[0, g, i])
+        np.testing.assert_array_equal(l_s[w], lt[0, g, i])
 
 
 def test_gqa_with_one_head_per_group_is_the_plain_path(oracle):
