@@ -73,6 +73,7 @@ def cpu_baseline(problem, cfg):
                    f"({nb * cfg.n_tokens} tokens): select {t1 - t0:.2f} s + forward "
                    f"{t2 - t1:.2f} s, double-precision attention"),
         "seconds": t2 - t0,
+        "extrapolated_full_workload_seconds": (t2 - t0) * cfg.batch / nb,
     }
 
 
@@ -132,8 +133,36 @@ def main():
     t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    sel_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    fwd_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    sel_all = sorted(e[0].elapsed_time(e[1]) for e in evs)
+    fwd_all = sorted(e[1].elapsed_time(e[2]) for e in evs)
+    sel_ms = sum(sel_all) / args.steps
+    fwd_ms = sum(fwd_all) / args.steps
+
+    # One cold step: a 1 GiB fill pushes the inputs out of L2 and the memory-side
+    # cache first (outside the timed region above).
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    flush.fill_(1)
+    cold = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    step(cold)
+    torch.cuda.synchronize()
+    del flush
+
+    # Sustained dense bf16 matrix rate of this machine (library GEMM on random
+    # operands), for context: clocks under matrix load are below nominal.
+    gemm_tflops = None
+    if is_bf16:
+        ga = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+        gb = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+        for _ in range(3):
+            torch.matmul(ga, gb)
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(10):
+            torch.matmul(ga, gb)
+        g1.record()
+        torch.cuda.synchronize()
+        gemm_tflops = 10 * 2 * 8192 ** 3 / (g0.elapsed_time(g1) * 1e-3) / 1e12
+        del ga, gb
     tokens = cfg.batch * cfg.n_tokens
     flops = cfg.fwd_flops()
     eff_tflops = flops / (fwd_ms * 1e-3) / 1e12
@@ -160,6 +189,15 @@ def main():
             "tokens_per_step": tokens,
         },
         "select_ms": sel_ms, "fwd_ms": fwd_ms,
+        "fwd_ms_median": fwd_all[len(fwd_all) // 2], "fwd_ms_min": fwd_all[0],
+        "select_ms_median": sel_all[len(sel_all) // 2], "select_ms_min": sel_all[0],
+        "cold_select_ms": cold[0].elapsed_time(cold[1]),
+        "cold_fwd_ms": cold[1].elapsed_time(cold[2]),
+        "dense_equivalent_tflops": (4 * cfg.batch * cfg.heads * cfg.n_tokens ** 2 * cfg.head_dim
+                                    / (fwd_ms * 1e-3) / 1e12),
+        "library_gemm_bf16_tflops": gemm_tflops,
+        "pct_of_library_gemm": (100.0 * eff_tflops / gemm_tflops) if gemm_tflops else None,
+        "hbm_frac_fwd": (traffic / (fwd_ms * 1e-3) / (HBM_PEAK_GBS * 1e9)) if traffic else None,
         "effective_tflops": eff_tflops,
         "pct_mfma_peak": 100.0 * eff_tflops / MFMA_BF16_PEAK_TFLOPS,
         "fwd_only_tokens_per_s": tokens / (fwd_ms * 1e-3),
