@@ -304,13 +304,16 @@ static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t*
 {
     const int G = select_group_size(g.n_blocks, D);
     const size_t lds = (size_t)G * (D + (size_t)g.n_blocks) * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // the attribute is per device; setting it twice (two host threads racing) is harmless
+    static bool attr_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
         hipError_t e = hipFuncSetAttribute((const void*)select_kernel<D>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kSelectLdsBudget);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[dev] = true;
     }
     dim3 grid((unsigned)(BH * ((g.n_blocks + G - 1) / G)));
     hipLaunchKernelGGL((select_kernel<D>), grid, dim3(256), lds, stream, qbar, kbar, sel_idx, g,

@@ -179,13 +179,16 @@ static hipError_t launch_coarse_t(const float* qbar, const float* kbar, const fl
 {
     const int G = coarse_group_size(g.n_blocks, D);
     if (G == 0) return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // the attribute is per device; setting it twice (two host threads racing) is harmless
+    static bool attr_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
         hipError_t e = hipFuncSetAttribute((const void*)coarse_kernel<D>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kCoarseLdsBudget);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[dev] = true;
     }
     dim3 grid((unsigned)(BH * ((g.n_blocks + G - 1) / G)));
     hipLaunchKernelGGL((coarse_kernel<D>), grid, dim3(256), coarse_lds_bytes(G, g.n_blocks, D),

@@ -115,6 +115,18 @@ def test_mfma_d128_tile_shapes(G, oracle, H, W, bh, bw, n):
     full_parity(G, oracle, cfg, q, k, v)
 
 
+@pytest.mark.parametrize("H,W,bh,bw,D,n", [
+    (80, 80, 8, 8, 64, 70),      # m = 100
+    (72, 128, 8, 16, 128, 68),   # m = 72
+])
+def test_mfma_more_than_64_attended_blocks(G, oracle, H, W, bh, bw, D, n):
+    """Above 64 attended blocks the matrix-core kernels visit the selection in
+    the given order instead of sorting it inside a wavefront."""
+    cfg = shape_ns(1, 2, H, W, bh, bw, D, n, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 600 + D))
+    full_parity(G, oracle, cfg, q, k, v)
+
+
 def test_mfma_d128_is_deterministic_and_order_invariant(G, oracle):
     cfg = shape_ns(1, 2, 32, 64, 8, 16, 128, 5, "bf16")
     q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 77))
