@@ -104,7 +104,9 @@ size_t mosaic_bsa_workspace_bytes(const mosaic_bsa_params *params, int op);
  *   workspace      device scratch of mosaic_bsa_workspace_bytes(.., OP_SELECT)
  *                  bytes; on return it holds the pooled q, fp32
  *                  [B, heads, m, D], at its start and the pooled k, fp32
- *                  [B, kv_heads, m, D], at the start of its second half.
+ *                  [B, kv_heads, m, D], at the byte offset of the pooled
+ *                  q's size rounded up to a multiple of 256; the rest is
+ *                  scratch.
  * Arithmetic is fixed so that indices are reproducible bit for bit: pooled
  * sums are fp32 adds in in-tile row-major order followed by one multiply by
  * 1/b; a score is the fp32 chain acc = fma(qbar[d], kbar[d], acc), d ascending.

@@ -68,9 +68,15 @@ bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// pooled q | pooled k | ranking keys (only where the selection needs them)
+size_t pooled_bytes(const Checked& c)
+{
+    return align_up((size_t)c.BH * c.g.n_blocks * c.D * sizeof(float));
+}
+
 size_t select_workspace(const Checked& c)
 {
-    return 2 * align_up((size_t)c.BH * c.g.n_blocks * c.D * sizeof(float));
+    return 2 * pooled_bytes(c) + align_up(bsa::select_scratch_bytes(c.g.n_blocks, c.BH));
 }
 
 size_t bwd_workspace(const Checked& c)
@@ -107,11 +113,12 @@ extern "C" int mosaic_bsa_select(const mosaic_bsa_params* params, const void* q,
 
     hipStream_t stream = (hipStream_t)hip_stream;
     float* qbar = (float*)workspace;
-    float* kbar = (float*)((char*)workspace + select_workspace(c) / 2);
+    float* kbar = (float*)((char*)workspace + pooled_bytes(c));
+    void* scratch = (char*)workspace + 2 * pooled_bytes(c);
     if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     if (c.g.n_select == 0) return MOSAIC_BSA_OK;
-    if (bsa::launch_select(qbar, kbar, sel_idx, c.g, c.D, c.BH, stream) != hipSuccess)
+    if (bsa::launch_select(qbar, kbar, sel_idx, scratch, c.g, c.D, c.BH, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     return MOSAIC_BSA_OK;
 }
@@ -155,7 +162,7 @@ namespace {
 
 // Workspace of the three-branch forward: 256-byte aligned parts in this order.
 struct ThreeBranchLayout {
-    size_t qbar, kbar, vbar, obar, lists, o_fg, o_l, total;
+    size_t qbar, kbar, vbar, obar, keys, lists, o_fg, o_l, total;
 };
 
 ThreeBranchLayout three_branch_layout(const Checked& c, int local_tiles)
@@ -172,6 +179,7 @@ ThreeBranchLayout three_branch_layout(const Checked& c, int local_tiles)
     w.kbar = take((size_t)c.BKV * m * c.D * 4);
     w.vbar = take((size_t)c.BKV * m * c.D * 4);
     w.obar = take((size_t)c.BH * m * c.D * 4);
+    w.keys = take(bsa::select_scratch_bytes(c.g.n_blocks, c.BH));
     w.lists = take((size_t)c.BH * m * (size_t)(local_tiles - 1) * 4);
     w.o_fg = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
     w.o_l = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
@@ -232,7 +240,8 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
         return MOSAIC_BSA_ERR_LAUNCH;
     // coarse branch, and the ranking it shares with the selection branch
     if (bsa::launch_coarse(qbar, kbar, vbar, obar, c.g, c.D, c.BH, stream) != hipSuccess ||
-        bsa::launch_select(qbar, kbar, sel_idx, c.g, c.D, c.BH, stream) != hipSuccess)
+        bsa::launch_select(qbar, kbar, sel_idx, ws + w.keys, c.g, c.D, c.BH, stream) !=
+            hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     // selection branch: one softmax over the selected blocks only
     bsa::Geom g_fg = c.g;

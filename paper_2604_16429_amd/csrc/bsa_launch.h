@@ -19,8 +19,11 @@ hipError_t launch_pool(bool is_bf16, const void* q, const void* k, float* qbar, 
 hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom& g, int D,
                            int64_t slices, hipStream_t stream);
 
-hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, const Geom& g,
-                         int D, int64_t BH, hipStream_t stream);
+// `scratch`: device memory of select_scratch_bytes(m, BH) bytes (0 for most
+// shapes: only 512 < m <= 4096 ranks through a global matrix of keys).
+size_t select_scratch_bytes(int m, int64_t BH);
+hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, void* scratch,
+                         const Geom& g, int D, int64_t BH, hipStream_t stream);
 
 // Any tile shape / head dim in {32, 64, 128} / dtype; fp32 vector arithmetic.
 hipError_t launch_fwd_generic(bool is_bf16, const void* q, const void* k, const void* v,

@@ -249,6 +249,142 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
 }
 
 // ---------------------------------------------------------------------------
+// Many blocks (512 < m <= 4096): the ranking keys of a row no longer fit the
+// registers of the fused kernel and its LDS footprint leaves one workgroup per
+// CU.  Two kernels instead: the scores of R query blocks against 256 key blocks
+// per workgroup, ranking keys written to a global scratch matrix [B*h, m, m]
+// (same pinned fma chain, same keys), then one wavefront per row extracts the n
+// best from registers.
+// ---------------------------------------------------------------------------
+constexpr int kScoreRows = 32;          // query blocks per scores workgroup
+constexpr int kBigSlots = 64;           // candidates per lane in topn_kernel: m <= 4096
+
+template <int D>
+__global__ __launch_bounds__(256) void scores_kernel(const float* __restrict__ qbar,
+                                                     const float* __restrict__ kbar,
+                                                     uint32_t* __restrict__ keys, Geom g)
+{
+    __shared__ __attribute__((aligned(16))) float q_s[kScoreRows * D];
+    const int m = g.n_blocks;
+    const int row_groups = (m + kScoreRows - 1) / kScoreRows, key_chunks = (m + 255) / 256;
+    // blockIdx.x = (batch*head * row_groups + row group) * key_chunks + key chunk
+    const int kc = blockIdx.x % key_chunks;
+    const int64_t t = blockIdx.x / key_chunks;
+    const int i0 = (int)(t % row_groups) * kScoreRows;
+    const int64_t bh_idx = t / row_groups;
+    const int rows = min(kScoreRows, m - i0);
+    qbar += (bh_idx * m + i0) * D;
+    kbar += kv_slice_of(g, bh_idx) * m * D;
+    keys += (bh_idx * m + i0) * (int64_t)m;
+
+    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) q_s[e] = qbar[e];
+    __syncthreads();
+
+    const int j = kc * 256 + (int)threadIdx.x;
+    if (j >= m) return;
+    float kr[D];
+    const float4* krow = (const float4*)(kbar + (int64_t)j * D);
+#pragma unroll
+    for (int d4 = 0; d4 < D / 4; ++d4) {
+        const float4 v = krow[d4];
+        kr[4 * d4 + 0] = v.x; kr[4 * d4 + 1] = v.y;
+        kr[4 * d4 + 2] = v.z; kr[4 * d4 + 3] = v.w;
+    }
+    for (int r = 0; r < rows; ++r) {
+        const float4* qrow = (const float4*)(q_s + r * D);
+        float acc = 0.0f;
+#pragma unroll
+        for (int d4 = 0; d4 < D / 4; ++d4) {
+            const float4 qv = qrow[d4];
+            acc = __builtin_fmaf(qv.x, kr[4 * d4 + 0], acc);
+            acc = __builtin_fmaf(qv.y, kr[4 * d4 + 1], acc);
+            acc = __builtin_fmaf(qv.z, kr[4 * d4 + 2], acc);
+            acc = __builtin_fmaf(qv.w, kr[4 * d4 + 3], acc);
+        }
+        keys[(int64_t)r * m + j] = (j == i0 + r && !g.own_is_candidate) ? 0u : rank_key(acc);
+    }
+}
+
+// Group GI of 8 register slots: remove slot `which` (0..7), then re-derive the
+// group's best key and its slot.  Equal keys keep the lower slot, i.e. the
+// smaller block index.
+template <int GI>
+__device__ __forceinline__ void regroup(uint32_t (&kreg)[kBigSlots], uint32_t (&gbest)[8],
+                                        uint32_t (&gslot)[8], uint32_t which)
+{
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        if (which == (uint32_t)u) kreg[GI * 8 + u] = 0u;
+    uint32_t b = kreg[GI * 8], sl = 0;
+#pragma unroll
+    for (int u = 1; u < 8; ++u)
+        if (kreg[GI * 8 + u] > b) { b = kreg[GI * 8 + u]; sl = (uint32_t)u; }
+    gbest[GI] = b;
+    gslot[GI] = (uint32_t)(GI * 8) + sl;
+}
+
+// One wavefront per query block (four per workgroup).  Lane l keeps the
+// candidates j == l (mod 64) in registers, slot j / 64, with the best of every
+// group of 8 slots cached; per round: wave-wide max of the lanes' best keys,
+// the winner is the lane holding it (smallest block index among equal keys),
+// and only the winner's group of 8 is rescanned.
+__global__ __launch_bounds__(256) void topn_kernel(const uint32_t* __restrict__ keys,
+                                                   int32_t* __restrict__ sel_idx, Geom g,
+                                                   int64_t rows_total)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows_total) return;                   // whole wavefront; no barriers below
+    const int m = g.n_blocks, n = g.n_select;
+    const uint32_t* krow = keys + row * m;
+    int32_t* dst = sel_idx + row * n;
+
+    uint32_t kreg[kBigSlots], gbest[8], gslot[8];
+#pragma unroll
+    for (int t = 0; t < kBigSlots; ++t) {
+        const int j = lane + 64 * t;
+        kreg[t] = j < m ? krow[j] : 0u;
+    }
+    regroup<0>(kreg, gbest, gslot, 8u); regroup<1>(kreg, gbest, gslot, 8u);
+    regroup<2>(kreg, gbest, gslot, 8u); regroup<3>(kreg, gbest, gslot, 8u);
+    regroup<4>(kreg, gbest, gslot, 8u); regroup<5>(kreg, gbest, gslot, 8u);
+    regroup<6>(kreg, gbest, gslot, 8u); regroup<7>(kreg, gbest, gslot, 8u);
+    auto lane_best = [&](uint32_t& best, uint32_t& best_j) {
+        best = gbest[0]; uint32_t slot = gslot[0];
+#pragma unroll
+        for (int gi = 1; gi < 8; ++gi)
+            if (gbest[gi] > best) { best = gbest[gi]; slot = gslot[gi]; }
+        best_j = best ? (uint32_t)lane + 64u * slot : 0xffffffffu;
+    };
+    uint32_t best, best_j;
+    lane_best(best, best_j);
+    for (int t = 0; t < n; ++t) {
+        const uint32_t top = wave_umax(best);
+        const uint64_t holders = __builtin_amdgcn_ballot_w64(best == top);
+        uint32_t win;
+        if (__builtin_expect(__builtin_popcountll(holders) == 1, 1))
+            win = __builtin_amdgcn_readlane(best_j, (int)__builtin_ctzll(holders));
+        else
+            win = wave_umin(best == top ? best_j : 0xffffffffu);
+        if (lane == 0) dst[t] = (int32_t)win;
+        if ((win & 63u) == (uint32_t)lane) {
+            const uint32_t slot = win >> 6, which = slot & 7u;   // wave-uniform values
+            switch (slot >> 3) {
+            case 0: regroup<0>(kreg, gbest, gslot, which); break;
+            case 1: regroup<1>(kreg, gbest, gslot, which); break;
+            case 2: regroup<2>(kreg, gbest, gslot, which); break;
+            case 3: regroup<3>(kreg, gbest, gslot, which); break;
+            case 4: regroup<4>(kreg, gbest, gslot, which); break;
+            case 5: regroup<5>(kreg, gbest, gslot, which); break;
+            case 6: regroup<6>(kreg, gbest, gslot, which); break;
+            default: regroup<7>(kreg, gbest, gslot, which); break;
+            }
+            lane_best(best, best_j);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------
 static constexpr size_t kSelectLdsBudget = 144 * 1024;
@@ -298,10 +434,30 @@ hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom&
     return hipGetLastError();
 }
 
+size_t select_scratch_bytes(int m, int64_t BH)
+{
+    // the two-kernel path keeps the ranking keys of every row in global memory
+    if (m <= 64 * kSlots || m > 64 * kBigSlots) return 0;
+    return (size_t)BH * (size_t)m * (size_t)m * 4;
+}
+
 template <int D>
 static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t* sel_idx,
-                                  const Geom& g, int64_t BH, hipStream_t stream)
+                                  uint32_t* keys, const Geom& g, int64_t BH, hipStream_t stream)
 {
+    if (select_scratch_bytes(g.n_blocks, BH) != 0) {
+        const int m = g.n_blocks;
+        const int64_t wgs = BH * ((m + kScoreRows - 1) / kScoreRows) * ((m + 255) / 256);
+        if (!keys || wgs >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((scores_kernel<D>), dim3((unsigned)wgs), dim3(256), 0, stream, qbar,
+                           kbar, keys, g);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const int64_t rows_total = BH * m;
+        hipLaunchKernelGGL(topn_kernel, dim3((unsigned)((rows_total + 3) / 4)), dim3(256), 0,
+                           stream, keys, sel_idx, g, rows_total);
+        return hipGetLastError();
+    }
     const int G = select_group_size(g.n_blocks, D);
     const size_t lds = (size_t)G * (D + (size_t)g.n_blocks) * 4;
     // the attribute is per device; setting it twice (two host threads racing) is harmless
@@ -321,13 +477,14 @@ static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t*
     return hipGetLastError();
 }
 
-hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, const Geom& g,
-                         int D, int64_t BH, hipStream_t stream)
+hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, void* scratch,
+                         const Geom& g, int D, int64_t BH, hipStream_t stream)
 {
+    uint32_t* keys = (uint32_t*)scratch;
     switch (D) {
-    case 32: return launch_select_t<32>(qbar, kbar, sel_idx, g, BH, stream);
-    case 64: return launch_select_t<64>(qbar, kbar, sel_idx, g, BH, stream);
-    case 128: return launch_select_t<128>(qbar, kbar, sel_idx, g, BH, stream);
+    case 32: return launch_select_t<32>(qbar, kbar, sel_idx, keys, g, BH, stream);
+    case 64: return launch_select_t<64>(qbar, kbar, sel_idx, keys, g, BH, stream);
+    case 128: return launch_select_t<128>(qbar, kbar, sel_idx, keys, g, BH, stream);
     }
     return hipErrorInvalidValue;
 }

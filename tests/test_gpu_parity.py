@@ -162,6 +162,31 @@ def test_ties_and_exact_arithmetic_selection(G, oracle):
     assert np.array_equal(G.gpu_select(cfg, qq, kq), oracle.select(s, qq, kq))
 
 
+@pytest.mark.parametrize("H,W,bh,bw,D,n,dtype", [
+    (80, 120, 4, 4, 32, 9, "fp32"),      # m = 600
+    (64, 128, 2, 2, 64, 40, "bf16"),     # m = 2048
+    (64, 256, 2, 2, 128, 5, "bf16"),     # m = 4096, the most the register path holds
+])
+def test_selection_with_many_blocks(G, oracle, H, W, bh, bw, D, n, dtype):
+    """512 < m <= 4096: ranking keys go through a global scratch matrix and the
+    top-n runs from registers; indices must still match bit for bit, ties
+    included."""
+    cfg = shape_ns(1, 2, H, W, bh, bw, D, n, dtype)
+    s = oracle.shape_of(cfg)
+    q, k, _ = rand_qkv(cfg, 900 + D)
+    if dtype == "bf16":
+        q, k = round_to_bf16(q), round_to_bf16(k)
+    assert np.array_equal(G.gpu_select(cfg, q, k), oracle.select(s, q, k))
+    rng = np.random.default_rng(901)
+    qq = (rng.integers(-8, 9, size=q.shape) / 4).astype(np.float32)
+    kq = (rng.integers(-2, 3, size=q.shape) / 4).astype(np.float32)   # many exact ties
+    assert np.array_equal(G.gpu_select(cfg, qq, kq), oracle.select(s, qq, kq))
+    ones = np.ones_like(k)                                            # every score ties
+    idx = G.gpu_select(cfg, q, ones)
+    for i in (0, 1, n, cfg.n_blocks - 1):
+        assert idx[0, 1, i].tolist() == [j for j in range(cfg.n_blocks) if j != i][:n]
+
+
 def test_pooled_means_in_workspace_are_bit_exact(G, oracle):
     import paper_2604_16429_amd as M
     from paper_2604_16429_amd import binding
@@ -179,7 +204,7 @@ def test_pooled_means_in_workspace_are_bit_exact(G, oracle):
     cnt = cfg.batch * cfg.heads * cfg.n_blocks * cfg.head_dim
     wsf = ws.view(torch.float32).cpu().numpy()
     assert np.array_equal(wsf[:cnt].reshape(oracle.pool(s, p.q).shape), oracle.pool(s, p.q))
-    half = nbytes // 8
+    half = (cnt * 4 + 255) // 256 * 256 // 4      # pooled q rounded up to 256 bytes
     assert np.array_equal(wsf[half:half + cnt].reshape(-1), oracle.pool(s, p.k).reshape(-1))
 
 
@@ -417,6 +442,7 @@ def test_grouped_query_attention(G, oracle, dtype, B, heads, kv_heads, H, W, bh,
     ("bf16", 1, 8, 2, 16, 256, 1, 128, 64, 5, 2, 2),  # block-contiguous 128-token blocks, grouped
     ("bf16", 2, 2, 0, 32, 64, 8, 16, 128, 3, 2, 2),   # head dim 128 matrix-core kernel
     ("bf16", 1, 2, 0, 120, 240, 8, 8, 64, 16, 3, 5),  # the 1.5 degree grid, m = 450
+    ("fp32", 1, 2, 0, 80, 120, 4, 4, 32, 6, 2, 2),    # m = 600: ranking through global scratch
 ])
 def test_three_branch_forward(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n, lh, lw):
     cfg = shape_ns(B, heads, H, W, bh, bw, D, n, dtype, kv_heads=kv_heads)
