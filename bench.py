@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3, help="configuration id (1-5: the benchmark configurations; 6, 7: the paper's stage-1 shape, block-contiguous and tiled; 8, 9: configurations 3 and 6 with 4 query heads per key/value head)")
+    ap.add_argument("--config", type=int, default=3, help="configuration id (1-5: the benchmark configurations; 6, 7: the paper's stage-1 shape, block-contiguous and tiled; 8, 9: configurations 3 and 6 with 4 query heads per key/value head; 10-12: the paper's stage-1, stage-2 and bottleneck attention layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--three-branch", type=int, nargs=2, metavar=("LOCAL_H", "LOCAL_W"),
                     help="also time the three-branch forward (coarse + selection + local "

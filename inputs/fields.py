@@ -99,6 +99,14 @@ CONFIGS = {
     8: GridConfig(8, 24, 16, 120, 240, 8, 8, 64, 16, "bf16", 6.0, 0.1,
                   sigma_member=0.05, kv_heads=4),
     9: GridConfig(9, 8, 16, 384, 128, 1, 128, 64, 24, "bf16", 6.0, 0.1, kv_heads=4),
+    # The attention layers of the paper's U-Net as the architecture table gives
+    # them (pixels, heads = dim / 64, grouped-query ratio 4, sparse block size
+    # 128, sparse block count), batch 24, block-contiguous: 10 = stage 1
+    # (49,152 pixels, 12 heads, 24 blocks), 11 = stage 2 (12,288 pixels, 16
+    # heads, 12 blocks), 12 = bottleneck (3,072 pixels, 20 heads, 4 blocks).
+    10: GridConfig(10, 24, 12, 384, 128, 1, 128, 64, 24, "bf16", 6.0, 0.1, kv_heads=3),
+    11: GridConfig(11, 24, 16, 96, 128, 1, 128, 64, 12, "bf16", 6.0, 0.1, kv_heads=4),
+    12: GridConfig(12, 24, 20, 24, 128, 1, 128, 64, 4, "bf16", 6.0, 0.1, kv_heads=5),
 }
 
 

@@ -478,3 +478,19 @@ def test_three_branch_gates_isolate_the_branches(G, oracle):
         got, _ = G.gpu_fwd_three_branch(cfg, q, k, v, gates, 2, 2)
         err = np.abs(got - branches[br]).max()
         assert err <= 2e-2, f"branch {br}: max-abs error {err}"
+
+
+def test_three_branch_paper_stage2_layer_reduced_batch(G, oracle):
+    """The paper's stage-2 attention layer (12,288 pixels in contiguous blocks
+    of 128, 12 selected blocks, local blocks of 1024, 4 query heads per
+    key/value head) on seeded smooth fields, one batch entry and one group."""
+    p = make_problem(11, batch=1, heads=4, kv_heads=1)
+    cfg = p.cfg
+    rng = np.random.default_rng(1111)
+    gates = rng.uniform(0.0, 1.0, size=(1, 4, cfg.n_tokens, 3)).astype(np.float32)
+    s = oracle.shape_of(cfg, own_is_candidate=True)
+    ref, sel_ref, _ = oracle.fwd_three_branch(s, p.q, p.k, p.v, gates, 8, 1)
+    got, sel = G.gpu_fwd_three_branch(cfg, p.q, p.k, p.v, gates, 8, 1)
+    assert np.array_equal(sel, sel_ref)
+    err = np.abs(got - ref).max()
+    assert err <= 2e-2, f"bf16 max-abs error {err}"
