@@ -46,35 +46,42 @@
 
 namespace bsa {
 
-namespace d128 {
+namespace q32 {
 
-constexpr int D = 128;
-constexpr int ROW_BYTES = D * 2;          // one token row of K or V in LDS
-constexpr int HALF_BYTES = 32 * ROW_BYTES;
-
-// 16-byte chunk swizzle of a 256-byte LDS row (16 chunks per row).  The K
-// fragment read takes the same chunk of 8 consecutive rows per 128 bytes of
-// bank width, the transposing V read 32 bytes (a chunk pair) of 4 consecutive
-// rows: the row's XOR mask is a bijection of row % 8 whose upper two bits
-// differ over any 4 aligned rows.
+// 16-byte chunk swizzle of an LDS row (16 chunks per 256-byte row, 8 per
+// 128-byte row).  The K fragment read takes the same chunk of 8 consecutive
+// rows per 128 bytes of bank width, the transposing V read 32 bytes (a chunk
+// pair) of 4 consecutive rows: the row's XOR mask is a bijection of row % 8
+// whose upper two bits differ over any 4 aligned rows.
 __device__ __forceinline__ int swz(int row, int chunk)
 {
     return chunk ^ (((row & 3) << 1) | ((row >> 2) & 1));
 }
 
-}  // namespace d128
+}  // namespace q32
 
-// wavefronts per workgroup: query blocks of 128 tokens
-constexpr int NW = 4;
-
-__global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
+// D: head dim; NW: wavefronts per workgroup = query block / 32.  Only D = 128
+// is instantiated: at D = 64 the same body fits three wavefronts per SIMD (155
+// registers) and measured no faster than the kernel with 64 query rows per
+// wavefront (blocks of 128 tokens: the same time; blocks of 64: 8 % slower).
+template <int D, int NW>
+__device__ __forceinline__ void fwd_mfma_q32_body(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
-    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, uint32_t n_units)
+    uint16_t* __restrict__ out, float* __restrict__ lse, const Geom& g, uint32_t n_units)
 {
-    using namespace d128;
-    static_assert(NW == 2 || NW == 4 || NW == 8, "a half tile is 8 loads, split between waves");
-    constexpr int LOADS = 8 / NW;          // loads per wavefront and half refill
+    using namespace q32;
+    constexpr int ROW_BYTES = D * 2;               // one token row of K or V in LDS
+    constexpr int HALF_BYTES = 32 * ROW_BYTES;
+    constexpr int KS = D / 16;                     // k-steps of S^T = K Q^T
+    constexpr int DT = D / 32;                     // 32-channel tiles of O^T
+    constexpr int NSLOT = KS + 2 * DT;             // MFMAs per step
+    constexpr int SPC = NSLOT / 8;                 // MFMA slots per chunk of weights
+    constexpr int SLAB_ROWS = 1024 / ROW_BYTES;    // token rows per 1 KiB load
+    constexpr int CHUNKS = ROW_BYTES / 16;         // 16-byte chunks per row
+    constexpr int HALF_LOADS = 32 / SLAB_ROWS;     // loads per half tile
+    static_assert(HALF_LOADS % NW == 0, "the loads of a half tile are split between the waves");
+    constexpr int LOADS = HALF_LOADS / NW;         // loads per wavefront and half refill
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[HALF_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[HALF_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[HALF_BYTES];
@@ -121,21 +128,24 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         return sel_row[c - 1];
     };
 
-    // Gather geometry.  One load moves 1 KiB = 4 token rows; lane l fills LDS
-    // chunk l of that slab, i.e. row l/16, swizzled chunk l%16, so it fetches
-    // the global chunk that swizzles to l%16 (the swizzle is an involution).  The tile width is a power of two >= 4,
-    // so the 4 tokens of a slab are contiguous in memory: a per-lane offset
-    // (two variants, by the parity of the slab inside the half) plus a
-    // wave-uniform offset of the slab's first token.
+    // Gather geometry.  One load moves 1 KiB = SLAB_ROWS token rows; lane l
+    // fills LDS chunk l of that slab, i.e. row l / CHUNKS, swizzled chunk
+    // l % CHUNKS, so it fetches the global chunk that swizzles to l % CHUNKS
+    // (the swizzle is an involution).  The tile width is a power of two >=
+    // SLAB_ROWS, so the tokens of a slab are contiguous in memory: a per-lane
+    // offset (two variants, by the parity of the slab inside the half: the
+    // swizzle looks at the row modulo 8) plus a wave-uniform offset of the
+    // slab's first token.
     const int bw_shift = __builtin_ctz((unsigned)g.block_w);
     uint32_t voff_par[2];
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
-        const int row = 4 * par + (lane >> 4);
-        voff_par[par] = (uint32_t)((lane >> 4) * ROW_BYTES + swz(row, lane & 15) * 16);
+        const int row = SLAB_ROWS * par + lane / CHUNKS;
+        voff_par[par] =
+            (uint32_t)((lane / CHUNKS) * ROW_BYTES + swz(row, lane % CHUNKS) * 16);
     }
     auto slab_offset = [&](int hh, int slab) -> uint32_t {   // first token of a slab, bytes
-        return (uint32_t)(sub_tile_pos(g, 32 * hh + 4 * slab) * ROW_BYTES);
+        return (uint32_t)(sub_tile_pos(g, 32 * hh + SLAB_ROWS * slab) * ROW_BYTES);
     };
     auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
         const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
@@ -163,7 +173,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
 
     // Q as B operand of S^T = K Q^T: lane (query l32, half) holds channels
     // 16 ks + 8 half .. + 7 of this wavefront's query row.
-    bf16x8 qf[8];
+    bf16x8 qf[KS];
     int64_t q_tok;
     {
         const int br = i / g.blocks_per_row, bc = i - br * g.blocks_per_row;
@@ -172,7 +182,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         const int rr = t >> bw_shift, cc = t & (g.block_w - 1);
         q_tok = tok0 + (int64_t)rr * g.grid_w + cc;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+        for (int ks = 0; ks < KS; ++ks)
             qf[ks] = *(const bf16x8*)(q + q_tok * D + 16 * ks + 8 * half);
     }
 
@@ -190,9 +200,9 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     const float c2 = g.scale * 1.4426950408889634f;
     const f32x16 zero16 = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
                            0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-    f32x16 oacc[4];         // [dt]: O^T tile, rows = channels 32 dt .., cols = queries
+    f32x16 oacc[DT];        // [dt]: O^T tile, rows = channels 32 dt .., cols = queries
 #pragma unroll
-    for (int a = 0; a < 4; ++a) oacc[a] = zero16;
+    for (int a = 0; a < DT; ++a) oacc[a] = zero16;
     float m_ref = -INFINITY, l_run = 0.0f;
 
     // V (transposing read): source lane s of 16-lane group gq supplies 8 bytes of
@@ -203,15 +213,15 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
 
     // fragments of one 32-key half: K rows as A operands of S^T (kf[ks]), V
     // through the transposing read as A operands of O^T (vf[dt][h], keys 16 h ..)
-    bf16x8 kf[8], vf[4][2];
+    bf16x8 kf[KS], vf[DT][2];
     auto read_k_half = [&](const unsigned char* lds_half) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+        for (int ks = 0; ks < KS; ++ks)
             kf[ks] = *(const bf16x8*)(lds_half + l32 * ROW_BYTES + swz(l32, 2 * ks + half) * 16);
     };
     auto read_v_half = [&](const unsigned char* lds_half) {
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 bf16x4 part[2];
@@ -250,10 +260,10 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         const bf16x8 zero8 = __builtin_bit_cast(bf16x8, make_uint4(0u, 0u, 0u, 0u));
         p[1][0] = zero8; p[1][1] = zero8;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) { vf[dt][0] = zero8; vf[dt][1] = zero8; }
+        for (int dt = 0; dt < DT; ++dt) { vf[dt][0] = zero8; vf[dt][1] = zero8; }
     }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < KS; ++ks)
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], ks == 0 ? zero16 : s[0], 0,
                                                        0, 0);
     __builtin_amdgcn_sched_barrier(0);
@@ -274,10 +284,20 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         m_ref = m_new;
         l_run *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
         return tile_weights(s[par], c2, -m_new, p[par]);
+    };
+
+    // The K fragment reads of the previous step are older than the 4 DT V reads
+    // issued after them, so "at most 4 DT - 1 outstanding" covers them (LDS
+    // operations complete in order; not so with a scalar load of the selection
+    // row in flight).
+    auto wait_k_reads = [&] {
+        if (!sorted) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        else if (DT == 4) asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
+        else asm volatile("s_waitcnt lgkmcnt(7)" ::: "memory");
     };
 
     // everything but this wavefront's most recent refill share has landed, and
@@ -289,9 +309,9 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     };
 
     // One step: tile J of the pair (key half J).  S of the next tile from the
-    // K fragments in registers (8 MFMAs), then the K fragments of the tile
+    // K fragments in registers (KS MFMAs), then the K fragments of the tile
     // after that are requested from k_next_lds; O += previous tile with the V
-    // fragments in registers (8 MFMAs), then the next V fragments are requested
+    // fragments in registers (2 DT MFMAs), then the next V fragments are requested
     // from v_next_lds.  `before_k` runs before the K request (wait for the
     // refill of that half), `early` right after the first MFMA (barrier and
     // refill issue).  The weights of tile J are spread behind the MFMAs.
@@ -307,12 +327,12 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         asm volatile("" : "+v"(f[0][0]), "+v"(f[0][1]));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kslot = 0; kslot < 16; ++kslot) {
-            if (kslot < 8) {
+        for (int kslot = 0; kslot < NSLOT; ++kslot) {
+            if (kslot < KS) {
                 s[1 - J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     kf[kslot], qf[kslot], kslot == 0 ? zero16 : s[1 - J], 0, 0, 0);
             } else {
-                const int dt = (kslot - 8) & 3, h = (kslot - 8) >> 2;
+                const int dt = (kslot - KS) % DT, h = (kslot - KS) / DT;
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][h], p[1 - J][h],
                                                                    oacc[dt], 0, 0, 0);
             }
@@ -320,16 +340,16 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
                 early();
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (kslot == 8) {
+            if (kslot == KS) {
                 // the S MFMAs have been issued: the K fragment registers are free
                 before_k();
                 read_k_half(k_next_lds);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (kslot & 1) {
+            if (kslot % SPC == SPC - 1) {
                 // exp2 of this chunk, fma of the next, pack and row sums of the
                 // previous one: nothing waits for the instruction before it
-                const int ch = kslot >> 1;
+                const int ch = kslot / SPC;
                 e[ch][0] = __builtin_amdgcn_exp2f(f[ch][0]);
                 e[ch][1] = __builtin_amdgcn_exp2f(f[ch][1]);
                 if (ch + 1 < 8) {
@@ -380,12 +400,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         rs = step(
             std::integral_constant<int, 0>{},
             [&] {
-                // K upper half: its fragment reads are older than the 16 V
-                // reads just issued, so "at most 15 outstanding" covers them
-                // (LDS operations complete in order; not so with a scalar
-                // load of the selection row in flight)
-                if (sorted) asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
-                else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                wait_k_reads();
                 __builtin_amdgcn_s_barrier();
                 refill_half(k1, o1, 1, k_lds1);
             },
@@ -410,8 +425,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         rs = step(
             std::integral_constant<int, 1>{},
             [&] {
-                if (sorted) asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
-                else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                wait_k_reads();
                 __builtin_amdgcn_s_barrier();
                 refill_half(k2, o2, 0, k_lds0);
             },
@@ -433,7 +447,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
             oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][h], p[1][h], oacc[dt], 0, 0,
                                                                0);
 
@@ -443,7 +457,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
         const float inv_l = (1.0f / (1.0f - kTruncLoss)) / l_tot;
         uint16_t* orow = out + q_tok * D;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 const int d = 32 * dt + 8 * r4 + 4 * half;
@@ -458,13 +472,22 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_d128_kernel(
     }
 }
 
+// head dim 128: query blocks of 128 tokens, two wavefronts per SIMD
+__global__ __launch_bounds__(256, 2) void fwd_mfma_d128_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+    const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
+    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, uint32_t n_units)
+{
+    fwd_mfma_q32_body<128, 4>(q, k, v, sel_idx, out, lse, g, n_units);
+}
+
 bool fwd_mfma_d128_supported(bool is_bf16, const Geom& g, int D)
 {
     // query block = 4 wavefronts x 32 rows; 64-key sub-tiles of whole tile rows
     // or 64-token runs of a row (the tile width is a power of two) whose 4-token
     // load slabs are contiguous (the
     // width is at least 4); buffer offsets inside a slice are 32-bit
-    return is_bf16 && D == 128 && g.block_tokens == 32 * NW &&
+    return is_bf16 && D == 128 && g.block_tokens == 128 &&
            (g.block_w & (g.block_w - 1)) == 0 && g.block_w >= 4 && g.n_tokens * D * 2 < ((int64_t)1 << 31);
 }
 
@@ -473,7 +496,7 @@ hipError_t launch_fwd_mfma_d128(const void* q, const void* k, const void* v,
                                 int64_t BH, hipStream_t stream)
 {
     dim3 grid((unsigned)(BH * g.n_blocks));
-    fwd_mfma_d128_kernel<<<grid, dim3(64 * NW), 0, stream>>>(
+    fwd_mfma_d128_kernel<<<grid, dim3(256), 0, stream>>>(
         (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
         (uint32_t)(BH / g.kv_group));
     return hipGetLastError();
