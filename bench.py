@@ -147,6 +147,19 @@ def main():
     torch.cuda.synchronize()
     del flush
 
+    # The matrix pipe's sustained rate on this machine: a register-resident bf16 MFMA
+    # loop (2 wavefronts per SIMD, mixed-sign operands), nothing else running.
+    probe_wgs, probe_iters = 2048, 4000
+    sink = torch.empty(probe_wgs * 256, dtype=torch.float32, device=dev)
+    M.mosaic_bsa_probe_mfma(sink, probe_wgs, 200)
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record()
+    M.mosaic_bsa_probe_mfma(sink, probe_wgs, probe_iters)
+    p1.record()
+    torch.cuda.synchronize()
+    probe_tflops = probe_wgs * 4 * 16 * probe_iters * 32768 / (p0.elapsed_time(p1) * 1e-3) / 1e12
+    del sink
+
     # Sustained dense bf16 matrix rate of this machine (library GEMM on random
     # operands), for context: clocks under matrix load are below nominal.
     gemm_tflops = None
@@ -195,6 +208,8 @@ def main():
         "cold_fwd_ms": cold[1].elapsed_time(cold[2]),
         "dense_equivalent_tflops": (4 * cfg.batch * cfg.heads * cfg.n_tokens ** 2 * cfg.head_dim
                                     / (fwd_ms * 1e-3) / 1e12),
+        "mfma_loop_bf16_tflops": probe_tflops,
+        "pct_of_mfma_loop": 100.0 * eff_tflops / probe_tflops,
         "library_gemm_bf16_tflops": gemm_tflops,
         "pct_of_library_gemm": (100.0 * eff_tflops / gemm_tflops) if gemm_tflops else None,
         "hbm_frac_fwd": (traffic / (fwd_ms * 1e-3) / (HBM_PEAK_GBS * 1e9)) if traffic else None,

@@ -196,6 +196,16 @@ int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params *params, int32_t local_h
                                 int32_t *sel_idx, void *workspace, size_t workspace_bytes,
                                 void *hip_stream);
 
+/*
+ * Measurement aid, not part of the attention path: a register-resident bf16
+ * matrix-core loop (no loads, no LDS, no vector work) whose rate is the most
+ * the matrix pipe sustains on the device at hand.  `workgroups` workgroups of
+ * 4 wavefronts each issue 16 * iters 32x32x16 bf16 MFMAs, i.e.
+ * workgroups * 4 * 16 * iters * 32768 flop in total; the caller times it.
+ *   sink   out  device, workgroups * 256 floats (keeps the loop alive)
+ */
+int mosaic_bsa_probe_mfma(float *sink, int32_t workgroups, int32_t iters, void *hip_stream);
+
 /* Static, human-readable text for a return code. */
 const char *mosaic_bsa_strerror(int code);
 

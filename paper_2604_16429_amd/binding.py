@@ -95,6 +95,8 @@ def load_library() -> ctypes.CDLL:
         lib.mosaic_bsa_fwd_three_branch.restype = i32
         lib.mosaic_bsa_fwd_three_branch.argtypes = (
             [pp, ctypes.c_int32, ctypes.c_int32] + [vp] * 7 + [sz, vp])
+        lib.mosaic_bsa_probe_mfma.restype = i32
+        lib.mosaic_bsa_probe_mfma.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
         lib.mosaic_bsa_strerror.restype = ctypes.c_char_p
         lib.mosaic_bsa_strerror.argtypes = [i32]
         _lib = lib
@@ -181,3 +183,8 @@ def mosaic_bsa_fwd_three_branch(params: Params, local_h: int, local_w: int, q, k
     _check(load_library().mosaic_bsa_fwd_three_branch(
         ctypes.byref(cp), int(local_h), int(local_w), _ptr(q), _ptr(k), _ptr(v), _ptr(gates),
         _ptr(out), _ptr(sel_idx), _ptr(workspace), wb, _stream(stream)))
+
+
+def mosaic_bsa_probe_mfma(sink, workgroups: int, iters: int, stream=None) -> None:
+    _check(load_library().mosaic_bsa_probe_mfma(_ptr(sink), int(workgroups), int(iters),
+                                                _stream(stream)))

@@ -287,6 +287,16 @@ extern "C" int mosaic_bsa_bwd(const mosaic_bsa_params* params, const void* q, co
     return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
 }
 
+extern "C" int mosaic_bsa_probe_mfma(float* sink, int32_t workgroups, int32_t iters,
+                                     void* hip_stream)
+{
+    if (!sink) return MOSAIC_BSA_ERR_NULL;
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return MOSAIC_BSA_ERR_SHAPE;
+    return bsa::launch_mfma_probe(sink, workgroups, iters, (hipStream_t)hip_stream) == hipSuccess
+               ? MOSAIC_BSA_OK
+               : MOSAIC_BSA_ERR_LAUNCH;
+}
+
 extern "C" const char* mosaic_bsa_strerror(int code)
 {
     switch (code) {

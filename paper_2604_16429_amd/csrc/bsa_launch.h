@@ -69,4 +69,8 @@ hipError_t launch_combine(bool is_bf16, const float* obar, const void* o_fg, con
                           const float* gates, void* out, const Geom& g, int D, int64_t BH,
                           hipStream_t stream);
 
+// Measurement aid: `workgroups` x 4 wavefronts, each issuing 16 * iters
+// v_mfma_f32_32x32x16_bf16 on register operands; sink: workgroups * 256 floats.
+hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, hipStream_t stream);
+
 }  // namespace bsa
