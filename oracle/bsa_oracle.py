@@ -378,19 +378,76 @@ def block_of_token(s):
     return out
 
 
-def fwd_three_branch(s, q, k, v, gates, local_h: int, local_w: int, scale: float = 0.0):
+def fwd_three_branch(s, q, k, v, gates, local_h: int, local_w: int, scale: float = 0.0,
+                     sel=None):
     """out = g_cg * o_cg + g_fg * o_fg + g_l * o_l, float64 [B,h,N,D]; also
     returns the selection and the three branch outputs.  k, v may carry fewer
-    heads than q (grouped query attention)."""
+    heads than q (grouped query attention).  A given `sel` replaces the
+    ranking (used to hold the selection fixed)."""
     k, v = expand_kv(k, s.heads), expand_kv(v, s.heads)
     B, h, N, D, b, m = _dims(s)
     gates = np.asarray(gates, dtype=np.float64)
     assert gates.shape == (B, h, N, 3)
     o_blocks, _ = coarse(s, q, k, v, scale)
     o_cg = o_blocks[:, :, block_of_token(s), :]
-    sel = select_all(s, q, k)
+    if sel is None:
+        sel = select_all(s, q, k)
     o_fg, _ = attend_lists(s, q, k, v, sel, scale)
     win = np.broadcast_to(local_lists(s, local_h, local_w), (B, h, m, local_h * local_w))
     o_l, _ = attend_lists(s, q, k, v, win, scale)
     out = gates[..., 0:1] * o_cg + gates[..., 1:2] * o_fg + gates[..., 2:3] * o_l
     return out, sel, (o_cg, o_fg, o_l)
+
+
+def tile_tokens(s):
+    """Token index of every (block, in-tile position), int64 [m, b]."""
+    B, h, N, D, b, m = _dims(s)
+    return np.array([[token_of(s, beta, tau) for tau in range(b)] for beta in range(m)],
+                    dtype=np.int64)
+
+
+def bwd_three_branch(s, q, k, v, gates, dout, sel, local_h: int, local_w: int,
+                     scale: float = 0.0):
+    """Gradients of sum(out * dout) with respect to q, k, v and the gates, the
+    selection held fixed (no gradient through the top-n; the coarse branch's
+    softmax and the pooling are differentiated).  The three-branch definition
+    is written out once more with float64 tensor operations (tile means,
+    softmax, matrix products over gathered tiles) and differentiated by the
+    library's reverse mode.  Returns (dq [B,h,N,D], dk, dv [B,kv_heads,N,D],
+    dgates [B,h,N,3], out [B,h,N,D]) as float64 numpy arrays."""
+    import torch
+    B, h, N, D, b, m = _dims(s)
+    kv_heads = k.shape[1]
+    group = h // kv_heads
+    sc = scale if scale > 0 else 1.0 / np.sqrt(D)
+    perm = torch.from_numpy(tile_tokens(s))                         # [m, b]
+    tq, tk, tv, tg = (torch.tensor(np.asarray(x), dtype=torch.float64, requires_grad=True)
+                      for x in (q, k, v, gates))
+    td = torch.tensor(np.asarray(dout), dtype=torch.float64)
+    qt = tq[:, :, perm]                                             # [B, h, m, b, D]
+    kt = tk[:, :, perm].repeat_interleave(group, dim=1)             # head a <- a // group
+    vt = tv[:, :, perm].repeat_interleave(group, dim=1)
+    gt, dt = tg[:, :, perm], td[:, :, perm]                         # [B, h, m, b, 3 / D]
+
+    # coarse branch: block-level attention over all m blocks on the tile means
+    qbar, kbar, vbar = qt.mean(dim=3), kt.mean(dim=3), vt.mean(dim=3)
+    abar = torch.softmax(sc * qbar @ kbar.transpose(-1, -2), dim=-1)
+    o_cg = (abar @ vbar)[:, :, :, None, :]                          # same row for the whole tile
+
+    def attend(lists):                                              # lists [B, h, m, cnt]
+        idx = torch.from_numpy(np.ascontiguousarray(lists, dtype=np.int64))
+        e = torch.arange(B)[:, None, None, None]
+        a = torch.arange(h)[None, :, None, None]
+        kk = kt[e, a, idx].reshape(B, h, m, -1, D)                  # gathered tiles
+        vv = vt[e, a, idx].reshape(B, h, m, -1, D)
+        p = torch.softmax(sc * qt @ kk.transpose(-1, -2), dim=-1)
+        return p @ vv
+
+    o_fg = attend(sel)
+    win = np.broadcast_to(local_lists(s, local_h, local_w), (B, h, m, local_h * local_w))
+    o_l = attend(win)
+    out_t = gt[..., 0:1] * o_cg + gt[..., 1:2] * o_fg + gt[..., 2:3] * o_l
+    (out_t * dt).sum().backward()
+    out = np.empty((B, h, N, D), dtype=np.float64)
+    out[:, :, perm.numpy()] = out_t.detach().numpy()
+    return (tq.grad.numpy(), tk.grad.numpy(), tv.grad.numpy(), tg.grad.numpy(), out)

@@ -599,3 +599,45 @@ def test_three_branch_sum_follows_the_gates(oracle):
     outc = oracle.fwd_three_branch(s, q, k, vc, gates, 2, 2)[0]
     np.testing.assert_allclose(outc, gates.sum(-1, keepdims=True) * np.repeat(vc, 2, axis=1),
                                rtol=0, atol=1e-6)
+
+
+def test_three_branch_gradients(oracle):
+    """The reverse-mode gradients of the three-branch form: its forward value
+    equals the loop-written forward, and the gradients match central
+    differences of THAT forward (selection held fixed) for every input."""
+    c = shape_ns(1, 4, 8, 16, 2, 4, 8, 3, kv_heads=2)      # m = 8, b = 8
+    s = oracle.shape_of(c, own_is_candidate=True)
+    rng = np.random.default_rng(60)
+    # values on a 2^-6 grid so that x +- 2^-9 is exact in fp32
+    q, dout = ((rng.integers(-96, 97, size=(1, 4, 128, 8)) / 64).astype(np.float32)
+               for _ in range(2))
+    k, v = ((rng.integers(-96, 97, size=(1, 2, 128, 8)) / 64).astype(np.float32)
+            for _ in range(2))
+    gates = (rng.integers(8, 65, size=(1, 4, 128, 3)) / 64).astype(np.float32)
+    out_ref, sel, _ = oracle.fwd_three_branch(s, q, k, v, gates, 2, 2)
+    dq, dk, dv, dg, out = oracle.bwd_three_branch(s, q, k, v, gates, dout, sel, 2, 2)
+    np.testing.assert_allclose(out, out_ref, rtol=0, atol=1e-6)   # fp32 pooled means vs float64
+    assert dk.shape == k.shape and dv.shape == v.shape and dg.shape == gates.shape
+    hstep = 2.0 ** -9
+
+    def loss(**kw):
+        a = dict(q=q, k=k, v=v, gates=gates)
+        a.update(kw)
+        o = oracle.fwd_three_branch(s, a["q"], a["k"], a["v"], a["gates"], 2, 2, sel=sel)[0]
+        return float((o * dout).sum())
+
+    for name, x, grad, spots in (
+            ("q", q, dq, [(0, 0, 0, 0), (0, 3, 77, 5), (0, 1, 127, 7)]),
+            ("k", k, dk, [(0, 0, 5, 1), (0, 1, 64, 3), (0, 1, 127, 0)]),
+            ("v", v, dv, [(0, 0, 9, 2), (0, 1, 100, 6)]),
+            ("gates", gates, dg, [(0, 0, 0, 0), (0, 2, 50, 1), (0, 3, 127, 2)])):
+        for pos in spots:
+            up, dn = x.copy(), x.copy()
+            up[pos] += hstep
+            dn[pos] -= hstep
+            fd = (loss(**{name: up}) - loss(**{name: dn})) / (2 * hstep)
+            assert abs(fd - grad[pos]) <= 2e-5 * max(1.0, abs(fd)), (name, pos, fd, grad[pos])
+    # gradient of a gate is the branch output dotted with the upstream gradient
+    _, _, (o_cg, o_fg, o_l) = oracle.fwd_three_branch(s, q, k, v, gates, 2, 2, sel=sel)
+    for br, o in enumerate((o_cg, o_fg, o_l)):
+        np.testing.assert_allclose(dg[..., br], (o * dout).sum(-1), rtol=0, atol=1e-6)
