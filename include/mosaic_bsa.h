@@ -180,9 +180,10 @@ int mosaic_bsa_bwd(const mosaic_bsa_params *params, const void *q, const void *k
  *   sel_idx       out  device, int32 [B, heads, m, n]: S_i in ranking order
  *   workspace          device scratch of
  *                      mosaic_bsa_three_branch_workspace_bytes(..) bytes (pooled
- *                      tensors, block lists and the two attention branches'
- *                      outputs in the element type of q); contents undefined
- *                      on return.
+ *                      tensors, block lists, the two attention branches'
+ *                      outputs in the element type of q and their
+ *                      log-sum-exps); on return it holds what
+ *                      mosaic_bsa_bwd_three_branch needs from the forward.
  * The branch outputs are rounded to the element type of q before the gated
  * sum, which runs in fp32.  Errors as for the other entry points; a local
  * group that does not divide the grid of tiles is MOSAIC_BSA_ERR_SHAPE.
@@ -195,6 +196,33 @@ int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params *params, int32_t local_h
                                 const void *v, const float *gates, void *out,
                                 int32_t *sel_idx, void *workspace, size_t workspace_bytes,
                                 void *hip_stream);
+
+/*
+ * Backward of mosaic_bsa_fwd_three_branch with sel_idx held fixed: no gradient
+ * flows through the top-n choice; the coarse branch's block softmax, the mean
+ * pooling and the gates are differentiated.
+ *   q, k, v, gates   in   device, as in the forward
+ *   dout             in   device, [B, heads, N, D], element type of q
+ *   sel_idx          in   device, as written by the forward
+ *   fwd_workspace    in   device, the forward's workspace after the forward
+ *                         call on the same inputs, contents intact
+ *   dq               out  device, [B, heads, N, D], element type of q
+ *   dk, dv           out  device, [B, kv_heads, N, D]
+ *   dgates           out  device, fp32 [B, heads, N, 3]: dout . branch output
+ *   workspace             device scratch of
+ *                         mosaic_bsa_three_branch_bwd_workspace_bytes(..) bytes
+ * The upstream gradients of the two attention branches (gate * dout) and the
+ * branches' partial gradients are rounded to the element type of q; every sum
+ * runs in a fixed order (no floating-point atomics).
+ */
+size_t mosaic_bsa_three_branch_bwd_workspace_bytes(const mosaic_bsa_params *params,
+                                                   int32_t local_h, int32_t local_w);
+int mosaic_bsa_bwd_three_branch(const mosaic_bsa_params *params, int32_t local_h,
+                                int32_t local_w, const void *q, const void *k,
+                                const void *v, const float *gates, const void *dout,
+                                const int32_t *sel_idx, const void *fwd_workspace,
+                                void *dq, void *dk, void *dv, float *dgates,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Measurement aid, not part of the attention path: a register-resident bf16

@@ -95,6 +95,12 @@ def load_library() -> ctypes.CDLL:
         lib.mosaic_bsa_fwd_three_branch.restype = i32
         lib.mosaic_bsa_fwd_three_branch.argtypes = (
             [pp, ctypes.c_int32, ctypes.c_int32] + [vp] * 7 + [sz, vp])
+        lib.mosaic_bsa_three_branch_bwd_workspace_bytes.restype = sz
+        lib.mosaic_bsa_three_branch_bwd_workspace_bytes.argtypes = [
+            pp, ctypes.c_int32, ctypes.c_int32]
+        lib.mosaic_bsa_bwd_three_branch.restype = i32
+        lib.mosaic_bsa_bwd_three_branch.argtypes = (
+            [pp, ctypes.c_int32, ctypes.c_int32] + [vp] * 12 + [sz, vp])
         lib.mosaic_bsa_probe_mfma.restype = i32
         lib.mosaic_bsa_probe_mfma.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
         lib.mosaic_bsa_strerror.restype = ctypes.c_char_p
@@ -188,3 +194,21 @@ def mosaic_bsa_fwd_three_branch(params: Params, local_h: int, local_w: int, q, k
 def mosaic_bsa_probe_mfma(sink, workgroups: int, iters: int, stream=None) -> None:
     _check(load_library().mosaic_bsa_probe_mfma(_ptr(sink), int(workgroups), int(iters),
                                                 _stream(stream)))
+
+
+def mosaic_bsa_three_branch_bwd_workspace_bytes(params: Params, local_h: int,
+                                                local_w: int) -> int:
+    cp = params.c_struct()
+    return int(load_library().mosaic_bsa_three_branch_bwd_workspace_bytes(
+        ctypes.byref(cp), int(local_h), int(local_w)))
+
+
+def mosaic_bsa_bwd_three_branch(params: Params, local_h: int, local_w: int, q, k, v, gates,
+                                dout, sel_idx, fwd_workspace, dq, dk, dv, dgates, workspace,
+                                stream=None, workspace_bytes=None) -> None:
+    cp = params.c_struct()
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(load_library().mosaic_bsa_bwd_three_branch(
+        ctypes.byref(cp), int(local_h), int(local_w), _ptr(q), _ptr(k), _ptr(v), _ptr(gates),
+        _ptr(dout), _ptr(sel_idx), _ptr(fwd_workspace), _ptr(dq), _ptr(dk), _ptr(dv),
+        _ptr(dgates), _ptr(workspace), wb, _stream(stream)))

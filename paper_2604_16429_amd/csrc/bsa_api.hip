@@ -162,7 +162,7 @@ namespace {
 
 // Workspace of the three-branch forward: 256-byte aligned parts in this order.
 struct ThreeBranchLayout {
-    size_t qbar, kbar, vbar, obar, keys, lists, o_fg, o_l, total;
+    size_t qbar, kbar, vbar, obar, keys, lists, o_fg, o_l, lse_fg, lse_l, total;
 };
 
 ThreeBranchLayout three_branch_layout(const Checked& c, int local_tiles)
@@ -183,6 +183,8 @@ ThreeBranchLayout three_branch_layout(const Checked& c, int local_tiles)
     w.lists = take((size_t)c.BH * m * (size_t)(local_tiles - 1) * 4);
     w.o_fg = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
     w.o_l = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
+    w.lse_fg = take((size_t)c.BH * (size_t)c.g.n_tokens * 4);
+    w.lse_l = take((size_t)c.BH * (size_t)c.g.n_tokens * 4);
     w.total = at;
     return w;
 }
@@ -246,13 +248,13 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
     // selection branch: one softmax over the selected blocks only
     bsa::Geom g_fg = c.g;
     g_fg.list_only = 1;
-    if (forward(c, g_fg, q, k, v, sel_idx, o_fg, nullptr, stream) != hipSuccess)
+    if (forward(c, g_fg, q, k, v, sel_idx, o_fg, (float*)(ws + w.lse_fg), stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     // local branch: the tile and the other tiles of its large block
     bsa::Geom g_l = c.g;
     g_l.n_select = local_tiles - 1;
     if (bsa::launch_local_lists(lists, c.g, local_h, local_w, c.BH, stream) != hipSuccess ||
-        forward(c, g_l, q, k, v, lists, o_l, nullptr, stream) != hipSuccess)
+        forward(c, g_l, q, k, v, lists, o_l, (float*)(ws + w.lse_l), stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     // gated sum
     if (bsa::launch_combine(c.is_bf16, obar, o_fg, o_l, gates, out, c.g, c.D, c.BH, stream) !=
@@ -260,6 +262,26 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
         return MOSAIC_BSA_ERR_LAUNCH;
     return MOSAIC_BSA_OK;
 }
+
+namespace {
+
+// The attention backward for geometry g (selection or lists held fixed);
+// scratch: bwd_workspace(c) bytes.
+hipError_t backward(const Checked& c, const bsa::Geom& g, const void* q, const void* k,
+                    const void* v, const void* out, const float* lse, const void* dout,
+                    const int32_t* lists, void* dq, void* dk, void* dv, void* scratch,
+                    hipStream_t stream)
+{
+    float* delta = (float*)scratch;
+    float* lse2 = (float*)((char*)scratch + bwd_workspace(c) / 2);
+    return bsa::bwd_mfma_supported(c.is_bf16, g, c.D)
+               ? bsa::launch_bwd_mfma(q, k, v, out, lse, dout, lists, dq, dk, dv, delta, lse2, g,
+                                      c.D, c.BH, stream)
+               : bsa::launch_bwd(c.is_bf16, q, k, v, out, lse, dout, lists, dq, dk, dv, delta, g,
+                                 c.D, c.BH, stream);
+}
+
+}  // namespace
 
 extern "C" int mosaic_bsa_bwd(const mosaic_bsa_params* params, const void* q, const void* k,
                               const void* v, const void* out, const float* lse, const void* dout,
@@ -275,16 +297,122 @@ extern "C" int mosaic_bsa_bwd(const mosaic_bsa_params* params, const void* q, co
         return MOSAIC_BSA_ERR_ALIGN;
     if (!workspace || workspace_bytes < bwd_workspace(c)) return MOSAIC_BSA_ERR_WORKSPACE;
 
+    return backward(c, c.g, q, k, v, out, lse, dout, sel_idx, dq, dk, dv, workspace,
+                    (hipStream_t)hip_stream) == hipSuccess
+               ? MOSAIC_BSA_OK
+               : MOSAIC_BSA_ERR_LAUNCH;
+}
+
+namespace {
+
+// Workspace of the three-branch backward: 256-byte aligned parts in this order.
+struct ThreeBranchBwdLayout {
+    size_t attn, do_fg, do_l, dq_l, dk_l, dv_l, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, total;
+};
+
+ThreeBranchBwdLayout three_branch_bwd_layout(const Checked& c)
+{
+    const size_t m = (size_t)c.g.n_blocks, N = (size_t)c.g.n_tokens, esz = c.is_bf16 ? 2 : 4;
+    ThreeBranchBwdLayout w;
+    size_t at = 0;
+    auto take = [&](size_t bytes) {
+        const size_t start = at;
+        at += align_up(bytes);
+        return start;
+    };
+    w.attn = take(bwd_workspace(c));                 // scratch of the attention backward kernels
+    w.do_fg = take((size_t)c.BH * N * c.D * esz);
+    w.do_l = take((size_t)c.BH * N * c.D * esz);
+    w.dq_l = take((size_t)c.BH * N * c.D * esz);
+    w.dk_l = take((size_t)c.BKV * N * c.D * esz);
+    w.dv_l = take((size_t)c.BKV * N * c.D * esz);
+    w.dobar = take((size_t)c.BH * m * c.D * 4);
+    w.a_mat = take((size_t)c.BH * m * m * 4);
+    w.ds_mat = take((size_t)c.BH * m * m * 4);
+    w.dqbar = take((size_t)c.BH * m * c.D * 4);
+    w.dkbar = take((size_t)c.BKV * m * c.D * 4);
+    w.dvbar = take((size_t)c.BKV * m * c.D * 4);
+    w.total = at;
+    return w;
+}
+
+}  // namespace
+
+extern "C" size_t mosaic_bsa_three_branch_bwd_workspace_bytes(const mosaic_bsa_params* params,
+                                                              int32_t local_h, int32_t local_w)
+{
+    Checked c;
+    if (check_params(params, &c, true) || check_local(params, local_h, local_w)) return 0;
+    if (bsa::coarse_bwd_group_size(c.g.n_blocks, c.D) == 0) return 0;
+    return three_branch_bwd_layout(c).total;
+}
+
+extern "C" int mosaic_bsa_bwd_three_branch(const mosaic_bsa_params* params, int32_t local_h,
+                                           int32_t local_w, const void* q, const void* k,
+                                           const void* v, const float* gates, const void* dout,
+                                           const int32_t* sel_idx, const void* fwd_workspace,
+                                           void* dq, void* dk, void* dv, float* dgates,
+                                           void* workspace, size_t workspace_bytes,
+                                           void* hip_stream)
+{
+    Checked c;
+    if (int rc = check_params(params, &c, true)) return rc;
+    if (int rc = check_local(params, local_h, local_w)) return rc;
+    if (!q || !k || !v || !gates || !dout || !sel_idx || !fwd_workspace || !dq || !dk || !dv ||
+        !dgates)
+        return MOSAIC_BSA_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(dout) || misaligned(dq) ||
+        misaligned(dk) || misaligned(dv) || misaligned(fwd_workspace) || misaligned(workspace))
+        return MOSAIC_BSA_ERR_ALIGN;
+    if (bsa::coarse_bwd_group_size(c.g.n_blocks, c.D) == 0) return MOSAIC_BSA_ERR_SHAPE;
+    const int local_tiles = local_h * local_w;
+    const ThreeBranchLayout f = three_branch_layout(c, local_tiles);
+    const ThreeBranchBwdLayout w = three_branch_bwd_layout(c);
+    if (!workspace || workspace_bytes < w.total) return MOSAIC_BSA_ERR_WORKSPACE;
+
     hipStream_t stream = (hipStream_t)hip_stream;
-    float* delta = (float*)workspace;
-    float* lse2 = (float*)((char*)workspace + bwd_workspace(c) / 2);
-    const hipError_t e =
-        bsa::bwd_mfma_supported(c.is_bf16, c.g, c.D)
-            ? bsa::launch_bwd_mfma(q, k, v, out, lse, dout, sel_idx, dq, dk, dv, delta, lse2, c.g,
-                                   c.D, c.BH, stream)
-            : bsa::launch_bwd(c.is_bf16, q, k, v, out, lse, dout, sel_idx, dq, dk, dv, delta, c.g,
-                              c.D, c.BH, stream);
-    return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
+    const char* fw = (const char*)fwd_workspace;
+    char* ws = (char*)workspace;
+    const float* qbar = (const float*)(fw + f.qbar);
+    const float* kbar = (const float*)(fw + f.kbar);
+    const float* vbar = (const float*)(fw + f.vbar);
+    const float* obar = (const float*)(fw + f.obar);
+    const int32_t* lists = (const int32_t*)(fw + f.lists);
+    float* dobar = (float*)(ws + w.dobar);
+
+    // upstream gradients of the two attention branches, gate gradients, and the
+    // coarse rows' gradient (gated block sums of dout)
+    if (bsa::launch_branch_grads(c.is_bf16, obar, fw + f.o_fg, fw + f.o_l, gates, dout,
+                                 ws + w.do_fg, ws + w.do_l, dgates, dobar, c.g, c.D, c.BH,
+                                 stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // selection branch -> dq, dk, dv
+    bsa::Geom g_fg = c.g;
+    g_fg.list_only = 1;
+    if (backward(c, g_fg, q, k, v, fw + f.o_fg, (const float*)(fw + f.lse_fg), ws + w.do_fg,
+                 sel_idx, dq, dk, dv, ws + w.attn, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // local branch -> scratch
+    bsa::Geom g_l = c.g;
+    g_l.n_select = local_tiles - 1;
+    if (backward(c, g_l, q, k, v, fw + f.o_l, (const float*)(fw + f.lse_l), ws + w.do_l, lists,
+                 ws + w.dq_l, ws + w.dk_l, ws + w.dv_l, ws + w.attn, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // coarse branch on the pooled tensors
+    if (bsa::launch_coarse_bwd(qbar, kbar, vbar, dobar, (float*)(ws + w.a_mat),
+                               (float*)(ws + w.ds_mat), (float*)(ws + w.dqbar),
+                               (float*)(ws + w.dkbar), (float*)(ws + w.dvbar), c.g, c.D, c.BH,
+                               stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    // dx = selection branch + local branch + the block's pooled gradient / b
+    if (bsa::launch_add_branches(c.is_bf16, dq, ws + w.dq_l, (const float*)(ws + w.dqbar), c.g,
+                                 c.D, c.BH, stream) != hipSuccess ||
+        bsa::launch_add_branches(c.is_bf16, dk, ws + w.dk_l, (const float*)(ws + w.dkbar), c.g,
+                                 c.D, c.BKV, stream) != hipSuccess ||
+        bsa::launch_add_branches(c.is_bf16, dv, ws + w.dv_l, (const float*)(ws + w.dvbar), c.g,
+                                 c.D, c.BKV, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    return MOSAIC_BSA_OK;
 }
 
 extern "C" int mosaic_bsa_probe_mfma(float* sink, int32_t workgroups, int32_t iters,

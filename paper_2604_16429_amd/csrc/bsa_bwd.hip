@@ -99,14 +99,19 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
     const int64_t blk = blockIdx.x / row_chunks;
     const int i = (int)(blk % g.n_blocks);
     const int64_t bh_idx = blk / g.n_blocks;
-    const int b = g.block_tokens, n = g.n_select;
+    const int b = g.block_tokens;
     const int quarter = threadIdx.x & 3;
     const int tau_q = rc * 64 + (threadIdx.x >> 2);
     const bool valid = tau_q < b;
     const int64_t base = bh_idx * g.n_tokens * D;
     const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
     const int64_t tok_q = token_of(g, i, valid ? tau_q : 0);
-    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
+    // The attended blocks: block i itself followed by its selected blocks, or,
+    // in list-only mode, exactly the listed blocks.
+    const int list_only = g.list_only;
+    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * g.n_select + list_only;
+    const int first = list_only ? sel_row[-1] : i;
+    const int n = g.n_select - list_only;        // blocks after the first
     const float c2 = g.scale * kLog2e;
 
     float qr[CPT], gr[CPT], acc[CPT];
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
     const float dl = delta[bh_idx * g.n_tokens + tok_q];
 
     for (int c = 0; c <= n; ++c) {
-        const int beta = (c == 0) ? i : sel_row[c - 1];
+        const int beta = (c == 0) ? first : sel_row[c - 1];
         for (int k0 = 0; k0 < b; k0 += KC) {
             const int kcnt = min(KC, b - k0);
             __syncthreads();
@@ -211,7 +216,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
         const int i_mine = i0 + threadIdx.x;
         bool hit = false;
         if (i_mine < m) {
-            hit = i_mine == j;
+            hit = i_mine == j && !g.list_only;    // list-only mode: the lists say it all
             const int32_t* row = sel_bh + (int64_t)i_mine * n;
             for (int r = 0; r < n; ++r) hit |= row[r] == j;
         }

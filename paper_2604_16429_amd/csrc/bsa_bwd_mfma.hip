@@ -185,7 +185,6 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int n = g.n_select;
     const int subs = g.block_tokens / 64;
 
     // workgroup -> (query slice, query block), key/value slices dealt to the 8
@@ -195,7 +194,12 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
     map_workgroup(g, blockIdx.x, (uint32_t)g.n_blocks, n_units, bh_idx, i);
     const int64_t base = bh_idx * g.n_tokens * D;
     const int64_t kv_base = kv_slice_of(g, bh_idx) * g.n_tokens * D;
-    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * n;
+    // The attended blocks: block i itself followed by its selected blocks, or,
+    // in list-only mode, exactly the listed blocks.
+    const int list_only = g.list_only;
+    const int32_t* sel_row = sel_idx + (bh_idx * g.n_blocks + i) * g.n_select + list_only;
+    const int first = list_only ? sel_row[-1] : i;
+    const int n = g.n_select - list_only;        // blocks after the first
     const uint32_t slice_bytes = (uint32_t)(g.n_tokens * D * 2);
     const __amdgpu_buffer_rsrc_t k_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(k + kv_base), 0, slice_bytes, 0x00020000);
@@ -211,7 +215,7 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
     const int pairs = (n + 1) * subs;
     auto origin_of_pair = [&](int c) -> uint32_t {   // attended block c / subs, sub-tile c % subs
         const int cb = c / subs, ct = c - cb * subs;
-        return origin_of(cb == 0 ? i : sel_row[cb - 1]) + (uint32_t)(sub_tile_first(g, ct) * (D * 2));
+        return origin_of(cb == 0 ? first : sel_row[cb - 1]) + (uint32_t)(sub_tile_first(g, ct) * (D * 2));
     };
 
     io.gather(k_rsrc, origin_of_pair(0), k_lds[0]);
@@ -399,7 +403,7 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
         const int i_mine = i0 + (int)threadIdx.x;
         bool hit = false;
         if (i_mine < m) {
-            hit = i_mine == j;
+            hit = i_mine == j && !g.list_only;    // list-only mode: the lists say it all
             const int32_t* row = sel_bh + (int64_t)i_mine * n;
             for (int r = 0; r < n; ++r) hit |= row[r] == j;
         }

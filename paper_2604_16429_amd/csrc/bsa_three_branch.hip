@@ -287,4 +287,430 @@ hipError_t launch_combine(bool is_bf16, const float* obar, const void* o_fg, con
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------
+// Backward of the three-branch output (selection held fixed).
+//   branch_grads_kernel  dO_fg = g_fg * dO and dO_l = g_l * dO (what the
+//                        attention backward kernels of the two branches take
+//                        as upstream gradient) and the gate gradients
+//                        dg_b = dO . o_b per token.
+//   gated_block_sum_kernel  d(coarse row of block i) = sum over the tokens l
+//                        of the block of g_cg(l) * dO_l, fp32 [B*h, m, D].
+//   coarse_bwd_rows_kernel  per query block: block attention a_i, da_ij =
+//                        dobar_i . vbar_j, ds_ij = a_ij (da_ij - sum_j a_ij
+//                        da_ij); writes a and ds (fp32 [B*h, m, m]) and
+//                        dqbar_i = scale * sum_j ds_ij kbar_j.
+//   coarse_bwd_cols_kernel  per key block and key/value slice: dvbar_j =
+//                        sum_i a_ij dobar_i and dkbar_j = scale * sum_i ds_ij
+//                        qbar_i, summed over the query heads of the group in
+//                        ascending order.
+//   add_branches_kernel  dx += dx_local + (pooled gradient of the token's
+//                        block) / b: the mean pooling hands every token of a
+//                        block the same share.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void branch_grads_kernel(
+    const float* __restrict__ obar, const T* __restrict__ o_fg, const T* __restrict__ o_l,
+    const float* __restrict__ gates, const T* __restrict__ dout, T* __restrict__ do_fg,
+    T* __restrict__ do_l, float* __restrict__ dgates, Geom g, int D, int64_t total)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool valid = e < total;
+    if (!valid) e = total - 1;                        // keep the lane groups whole
+    const int per_row = D / VEC;                      // lanes per token: a power of two <= 32
+    const int64_t row = e / per_row;
+    const int ch = (int)(e - row * per_row) * VEC;
+    const int64_t bh = row / g.n_tokens;
+    const int64_t tok = row - bh * g.n_tokens;
+    const int gr = (int)(tok / g.grid_w), gc = (int)(tok - (int64_t)gr * g.grid_w);
+    const int beta = (gr / g.block_h) * g.blocks_per_row + gc / g.block_w;
+    const float g_fg = gates[row * 3 + 1], g_l = gates[row * 3 + 2];
+    const float* ob = obar + (bh * g.n_blocks + beta) * D + ch;
+    float d_cg = 0.0f, d_fg = 0.0f, d_l = 0.0f;
+#pragma unroll
+    for (int v = 0; v < VEC; v += 4) {
+        const float4 up = load4(dout + row * D + ch + v);
+        const float4 a = *(const float4*)(ob + v);
+        const float4 f = load4(o_fg + row * D + ch + v);
+        const float4 l = load4(o_l + row * D + ch + v);
+        d_cg += up.x * a.x + up.y * a.y + up.z * a.z + up.w * a.w;
+        d_fg += up.x * f.x + up.y * f.y + up.z * f.z + up.w * f.w;
+        d_l += up.x * l.x + up.y * l.y + up.z * l.z + up.w * l.w;
+        if (valid) {
+            store4(do_fg + row * D + ch + v,
+                   make_float4(g_fg * up.x, g_fg * up.y, g_fg * up.z, g_fg * up.w));
+            store4(do_l + row * D + ch + v,
+                   make_float4(g_l * up.x, g_l * up.y, g_l * up.z, g_l * up.w));
+        }
+    }
+    for (int off = per_row >> 1; off >= 1; off >>= 1) {
+        d_cg += __shfl_xor(d_cg, off);
+        d_fg += __shfl_xor(d_fg, off);
+        d_l += __shfl_xor(d_l, off);
+    }
+    if (valid && ch == 0) {
+        dgates[row * 3 + 0] = d_cg;
+        dgates[row * 3 + 1] = d_fg;
+        dgates[row * 3 + 2] = d_l;
+    }
+}
+
+// One thread per (block, group of VEC channels); tokens in in-tile order.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void gated_block_sum_kernel(const T* __restrict__ dout,
+                                                              const float* __restrict__ gates,
+                                                              float* __restrict__ dobar, Geom g,
+                                                              int D, int64_t total)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    const int groups = D / VEC;
+    const int64_t blk = e / groups;                   // bh * m + beta
+    const int ch = (int)(e - blk * groups) * VEC;
+    const int64_t bh = blk / g.n_blocks;
+    const int beta = (int)(blk - bh * g.n_blocks);
+    float acc[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc[c] = 0.0f;
+    for (int tau = 0; tau < g.block_tokens; ++tau) {
+        const int64_t row = bh * g.n_tokens + token_of(g, beta, tau);
+        const float w = gates[row * 3 + 0];
+#pragma unroll
+        for (int v = 0; v < VEC; v += 4) {
+            const float4 up = load4(dout + row * D + ch + v);
+            acc[v + 0] = fmaf(w, up.x, acc[v + 0]);
+            acc[v + 1] = fmaf(w, up.y, acc[v + 1]);
+            acc[v + 2] = fmaf(w, up.z, acc[v + 2]);
+            acc[v + 3] = fmaf(w, up.w, acc[v + 3]);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; v += 4)
+        *(float4*)(dobar + blk * D + ch + v) =
+            make_float4(acc[v], acc[v + 1], acc[v + 2], acc[v + 3]);
+}
+
+// Same workgroup shape as coarse_kernel (G <= 8 query blocks of one slice).
+// LDS: 2*G*D (pooled queries, dobar rows) + (1024/D)*G*D (partials) +
+// 2*G*m (weights, ds) floats.
+template <int D>
+__global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
+    const float* __restrict__ qbar, const float* __restrict__ kbar,
+    const float* __restrict__ vbar, const float* __restrict__ dobar, float* __restrict__ a_out,
+    float* __restrict__ ds_out, float* __restrict__ dqbar, Geom g, int G)
+{
+    constexpr int CG = D / 4, JP = 256 / CG;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int m = g.n_blocks;
+    float* q_s = (float*)smem;                       // [G][D]
+    float* do_s = q_s + G * D;                       // [G][D]
+    float* red_s = do_s + G * D;                     // [JP][G][D]
+    float* sc_s = red_s + JP * G * D;                // [G][m]: scores -> weights a
+    float* da_s = sc_s + G * m;                      // [G][m]: da -> ds
+
+    const int groups = (m + G - 1) / G;
+    const int64_t bh_idx = blockIdx.x / groups;
+    const int i0 = (int)(blockIdx.x - bh_idx * groups) * G;
+    const int rows = min(G, m - i0);
+    const int64_t kv = kv_slice_of(g, bh_idx);
+    kbar += kv * m * D;
+    vbar += kv * m * D;
+    const int64_t row0 = bh_idx * m + i0;
+
+    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) {
+        q_s[e] = qbar[row0 * D + e];
+        do_s[e] = dobar[row0 * D + e];
+    }
+    __syncthreads();
+
+    // scores (base-2 domain) and da_ij = dobar_i . vbar_j
+    const float c2 = g.scale * kLog2e;
+    for (int j = threadIdx.x; j < m; j += blockDim.x) {
+        float kr[D];
+#pragma unroll
+        for (int d4 = 0; d4 < D / 4; ++d4) {
+            const float4 t = *(const float4*)(kbar + (int64_t)j * D + 4 * d4);
+            kr[4 * d4 + 0] = t.x; kr[4 * d4 + 1] = t.y; kr[4 * d4 + 2] = t.z; kr[4 * d4 + 3] = t.w;
+        }
+        for (int r = 0; r < rows; ++r) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) acc = fmaf(q_s[r * D + d], kr[d], acc);
+            sc_s[r * m + j] = acc * c2;
+        }
+#pragma unroll
+        for (int d4 = 0; d4 < D / 4; ++d4) {
+            const float4 t = *(const float4*)(vbar + (int64_t)j * D + 4 * d4);
+            kr[4 * d4 + 0] = t.x; kr[4 * d4 + 1] = t.y; kr[4 * d4 + 2] = t.z; kr[4 * d4 + 3] = t.w;
+        }
+        for (int r = 0; r < rows; ++r) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) acc = fmaf(do_s[r * D + d], kr[d], acc);
+            da_s[r * m + j] = acc;
+        }
+    }
+    __syncthreads();
+
+    // softmax weights and sum_j a_ij da_ij, one wavefront per row
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = wave; r < rows; r += 4) {
+        float* row = sc_s + r * m;
+        float mx = -INFINITY;
+        for (int j = lane; j < m; j += 64) mx = fmaxf(mx, row[j]);
+        mx = wave_max(mx);
+        float sum = 0.0f;
+        for (int j = lane; j < m; j += 64) {
+            const float w = __builtin_amdgcn_exp2f(row[j] - mx);
+            row[j] = w;
+            sum += w;
+        }
+        const float inv = 1.0f / wave_sum(sum);
+        float dot = 0.0f;
+        for (int j = lane; j < m; j += 64) {
+            const float a = row[j] * inv;
+            row[j] = a;
+            dot = fmaf(a, da_s[r * m + j], dot);
+        }
+        dot = wave_sum(dot);
+        // ds_ij, and both matrices to global memory for the column pass
+        float* a_row = a_out + (row0 + r) * (int64_t)m;
+        float* ds_row = ds_out + (row0 + r) * (int64_t)m;
+        for (int j = lane; j < m; j += 64) {
+            const float a = row[j];
+            const float ds = a * (da_s[r * m + j] - dot);
+            da_s[r * m + j] = ds;
+            a_row[j] = a;
+            ds_row[j] = ds;
+        }
+    }
+    __syncthreads();
+
+    // dqbar_i = scale * sum_j ds_ij kbar_j
+    const int cg = threadIdx.x % CG, jp = threadIdx.x / CG;
+    float4 acc[kCoarseRows];
+#pragma unroll
+    for (int r = 0; r < kCoarseRows; ++r) acc[r] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int j = jp; j < m; j += JP) {
+        const float4 val = *(const float4*)(kbar + (int64_t)j * D + 4 * cg);
+#pragma unroll
+        for (int r = 0; r < kCoarseRows; ++r) {
+            if (r < rows) {
+                const float w = da_s[r * m + j];
+                acc[r].x = fmaf(w, val.x, acc[r].x);
+                acc[r].y = fmaf(w, val.y, acc[r].y);
+                acc[r].z = fmaf(w, val.z, acc[r].z);
+                acc[r].w = fmaf(w, val.w, acc[r].w);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kCoarseRows; ++r)
+        if (r < rows) *(float4*)(red_s + ((jp * G + r) * D) + 4 * cg) = acc[r];
+    __syncthreads();
+    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) {
+        const int r = e / D, d = e - r * D;
+        float sum = 0.0f;
+        for (int p = 0; p < JP; ++p) sum += red_s[(p * G + r) * D + d];
+        dqbar[(row0 + r) * D + d] = sum * g.scale;
+    }
+}
+
+static size_t coarse_bwd_lds_bytes(int G, int m, int D)
+{
+    return ((size_t)2 * G * D + (size_t)(1024 / D) * G * D + (size_t)2 * G * m) * 4;
+}
+
+int coarse_bwd_group_size(int m, int D)
+{
+    for (int G = kCoarseRows; G >= 1; G >>= 1)
+        if (coarse_bwd_lds_bytes(G, m, D) <= kCoarseLdsBudget) return G;
+    return 0;
+}
+
+// One workgroup per (key/value slice, 8 consecutive key blocks).  Thread =
+// (channel quad, partition of the query blocks); columns j0..j0+7 of a and ds
+// are 32 contiguous bytes per query block.
+template <int D>
+__global__ __launch_bounds__(256) void coarse_bwd_cols_kernel(
+    const float* __restrict__ qbar, const float* __restrict__ dobar,
+    const float* __restrict__ a_in, const float* __restrict__ ds_in, float* __restrict__ dkbar,
+    float* __restrict__ dvbar, Geom g)
+{
+    constexpr int CG = D / 4, IP = 256 / CG, C = kCoarseRows;
+    __shared__ __attribute__((aligned(16))) float red_s[2 * IP * C * D];
+    const int m = g.n_blocks;
+    const int groups = (m + C - 1) / C;
+    const int64_t kv = blockIdx.x / groups;           // key/value slice
+    const int j0 = (int)(blockIdx.x - kv * groups) * C;
+    const int cols = min(C, m - j0);
+    const int64_t kv_heads = g.heads / g.kv_group;
+    const int64_t bh_first = (kv / kv_heads) * g.heads + (kv % kv_heads) * g.kv_group;
+    const int cg = threadIdx.x % CG, ip = threadIdx.x / CG;
+
+    float4 acc_k[C], acc_v[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        acc_k[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        acc_v[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+    // query heads of the group in ascending order, query blocks ascending inside a partition
+    for (int gq = 0; gq < g.kv_group; ++gq) {
+        const int64_t bh = bh_first + gq;
+        for (int i = ip; i < m; i += IP) {
+            const float4 q4 = *(const float4*)(qbar + (bh * m + i) * D + 4 * cg);
+            const float4 d4 = *(const float4*)(dobar + (bh * m + i) * D + 4 * cg);
+            const float* a_row = a_in + (bh * m + i) * (int64_t)m + j0;
+            const float* s_row = ds_in + (bh * m + i) * (int64_t)m + j0;
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                if (c < cols) {
+                    const float a = a_row[c], ds = s_row[c];
+                    acc_v[c].x = fmaf(a, d4.x, acc_v[c].x);
+                    acc_v[c].y = fmaf(a, d4.y, acc_v[c].y);
+                    acc_v[c].z = fmaf(a, d4.z, acc_v[c].z);
+                    acc_v[c].w = fmaf(a, d4.w, acc_v[c].w);
+                    acc_k[c].x = fmaf(ds, q4.x, acc_k[c].x);
+                    acc_k[c].y = fmaf(ds, q4.y, acc_k[c].y);
+                    acc_k[c].z = fmaf(ds, q4.z, acc_k[c].z);
+                    acc_k[c].w = fmaf(ds, q4.w, acc_k[c].w);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        *(float4*)(red_s + ((ip * C + c) * D) + 4 * cg) = acc_k[c];
+        *(float4*)(red_s + IP * C * D + ((ip * C + c) * D) + 4 * cg) = acc_v[c];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < cols * D; e += blockDim.x) {
+        const int c = e / D, d = e - c * D;
+        float sk = 0.0f, sv = 0.0f;
+        for (int p = 0; p < IP; ++p) {
+            sk += red_s[(p * C + c) * D + d];
+            sv += red_s[IP * C * D + (p * C + c) * D + d];
+        }
+        dkbar[(kv * m + j0 + c) * D + d] = sk * g.scale;
+        dvbar[(kv * m + j0 + c) * D + d] = sv;
+    }
+}
+
+// dx[row] += dx_other[row] + pooled[slice, block of the token] / b
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void add_branches_kernel(T* __restrict__ dx,
+                                                           const T* __restrict__ dx_other,
+                                                           const float* __restrict__ pooled,
+                                                           Geom g, int D, int64_t total)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    const int per_row = D / VEC;
+    const int64_t row = e / per_row;
+    const int ch = (int)(e - row * per_row) * VEC;
+    const int64_t slice = row / g.n_tokens;
+    const int64_t tok = row - slice * g.n_tokens;
+    const int gr = (int)(tok / g.grid_w), gc = (int)(tok - (int64_t)gr * g.grid_w);
+    const int beta = (gr / g.block_h) * g.blocks_per_row + gc / g.block_w;
+    const float inv_b = 1.0f / (float)g.block_tokens;
+    const float* pb = pooled + (slice * g.n_blocks + beta) * D + ch;
+#pragma unroll
+    for (int v = 0; v < VEC; v += 4) {
+        const float4 a = load4(dx + row * D + ch + v);
+        const float4 o = load4(dx_other + row * D + ch + v);
+        const float4 p = *(const float4*)(pb + v);
+        store4(dx + row * D + ch + v,
+               make_float4(a.x + o.x + p.x * inv_b, a.y + o.y + p.y * inv_b,
+                           a.z + o.z + p.z * inv_b, a.w + o.w + p.w * inv_b));
+    }
+}
+
+hipError_t launch_branch_grads(bool is_bf16, const float* obar, const void* o_fg, const void* o_l,
+                               const float* gates, const void* dout, void* do_fg, void* do_l,
+                               float* dgates, float* dobar, const Geom& g, int D, int64_t BH,
+                               hipStream_t stream)
+{
+    if (is_bf16) {
+        typedef uint16_t T;
+        const int64_t total = BH * g.n_tokens * (D / 8);
+        hipLaunchKernelGGL((branch_grads_kernel<T, 8>), dim3((unsigned)((total + 255) / 256)),
+                           dim3(256), 0, stream, obar, (const T*)o_fg, (const T*)o_l, gates,
+                           (const T*)dout, (T*)do_fg, (T*)do_l, dgates, g, D, total);
+        const int64_t blocks = BH * g.n_blocks * (D / 8);
+        hipLaunchKernelGGL((gated_block_sum_kernel<T, 8>), dim3((unsigned)((blocks + 255) / 256)),
+                           dim3(256), 0, stream, (const T*)dout, gates, dobar, g, D, blocks);
+    } else {
+        typedef float T;
+        const int64_t total = BH * g.n_tokens * (D / 4);
+        hipLaunchKernelGGL((branch_grads_kernel<T, 4>), dim3((unsigned)((total + 255) / 256)),
+                           dim3(256), 0, stream, obar, (const T*)o_fg, (const T*)o_l, gates,
+                           (const T*)dout, (T*)do_fg, (T*)do_l, dgates, g, D, total);
+        const int64_t blocks = BH * g.n_blocks * (D / 4);
+        hipLaunchKernelGGL((gated_block_sum_kernel<T, 4>), dim3((unsigned)((blocks + 255) / 256)),
+                           dim3(256), 0, stream, (const T*)dout, gates, dobar, g, D, blocks);
+    }
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, const float* vbar,
+                                      const float* dobar, float* a_mat, float* ds_mat,
+                                      float* dqbar, float* dkbar, float* dvbar, const Geom& g,
+                                      int64_t BH, hipStream_t stream)
+{
+    const int G = coarse_bwd_group_size(g.n_blocks, D);
+    if (G == 0) return hipErrorInvalidValue;
+    static bool attr_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        hipError_t e = hipFuncSetAttribute((const void*)coarse_bwd_rows_kernel<D>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kCoarseLdsBudget);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    const int m = g.n_blocks;
+    hipLaunchKernelGGL((coarse_bwd_rows_kernel<D>), dim3((unsigned)(BH * ((m + G - 1) / G))),
+                       dim3(256), coarse_bwd_lds_bytes(G, m, D), stream, qbar, kbar, vbar, dobar,
+                       a_mat, ds_mat, dqbar, g, G);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t BKV = BH / g.kv_group;
+    hipLaunchKernelGGL((coarse_bwd_cols_kernel<D>),
+                       dim3((unsigned)(BKV * ((m + kCoarseRows - 1) / kCoarseRows))), dim3(256), 0,
+                       stream, qbar, dobar, a_mat, ds_mat, dkbar, dvbar, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* vbar,
+                             const float* dobar, float* a_mat, float* ds_mat, float* dqbar,
+                             float* dkbar, float* dvbar, const Geom& g, int D, int64_t BH,
+                             hipStream_t stream)
+{
+    switch (D) {
+    case 32: return launch_coarse_bwd_t<32>(qbar, kbar, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
+    case 64: return launch_coarse_bwd_t<64>(qbar, kbar, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
+    case 128: return launch_coarse_bwd_t<128>(qbar, kbar, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_add_branches(bool is_bf16, void* dx, const void* dx_other, const float* pooled,
+                               const Geom& g, int D, int64_t slices, hipStream_t stream)
+{
+    if (is_bf16) {
+        const int64_t total = slices * g.n_tokens * (D / 8);
+        hipLaunchKernelGGL((add_branches_kernel<uint16_t, 8>),
+                           dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                           (uint16_t*)dx, (const uint16_t*)dx_other, pooled, g, D, total);
+    } else {
+        const int64_t total = slices * g.n_tokens * (D / 4);
+        hipLaunchKernelGGL((add_branches_kernel<float, 4>), dim3((unsigned)((total + 255) / 256)),
+                           dim3(256), 0, stream, (float*)dx, (const float*)dx_other, pooled, g, D,
+                           total);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace bsa

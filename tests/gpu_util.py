@@ -85,3 +85,27 @@ def gpu_fwd_three_branch(cfg, q, k, v, gates, local_h, local_w, softmax_scale=0.
     M.mosaic_bsa_fwd_three_branch(p, local_h, local_w, q_d, k_d, v_d, g_d, out, idx, ws)
     torch.cuda.synchronize()
     return out.float().cpu().numpy(), idx.cpu().numpy()
+
+
+def gpu_three_branch_fwd_bwd(cfg, q, k, v, gates, dout, local_h, local_w):
+    """Three-branch forward then backward on the GPU; returns (out, sel, dq, dk,
+    dv, dgates) as numpy arrays."""
+    p = params_of(cfg)
+    q_d, k_d, v_d, do_d = (to_dev(x, cfg) for x in (q, k, v, dout))
+    g_d = torch.from_numpy(np.ascontiguousarray(gates, dtype=np.float32)).to("cuda")
+    out = torch.full_like(q_d, float("nan"))
+    idx = torch.full((cfg.batch, cfg.heads, p.n_blocks, p.n_select), -1, dtype=torch.int32,
+                     device="cuda")
+    ws_f = torch.empty(M.mosaic_bsa_three_branch_workspace_bytes(p, local_h, local_w),
+                       dtype=torch.uint8, device="cuda")
+    M.mosaic_bsa_fwd_three_branch(p, local_h, local_w, q_d, k_d, v_d, g_d, out, idx, ws_f)
+    nbytes = M.mosaic_bsa_three_branch_bwd_workspace_bytes(p, local_h, local_w)
+    assert nbytes > 0
+    ws_b = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q_d, k_d, v_d))
+    dg = torch.full_like(g_d, float("nan"))
+    M.mosaic_bsa_bwd_three_branch(p, local_h, local_w, q_d, k_d, v_d, g_d, do_d, idx, ws_f,
+                                  dq, dk, dv, dg, ws_b)
+    torch.cuda.synchronize()
+    return (out.float().cpu().numpy(), idx.cpu().numpy(), dq.float().cpu().numpy(),
+            dk.float().cpu().numpy(), dv.float().cpu().numpy(), dg.cpu().numpy())

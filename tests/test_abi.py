@@ -122,7 +122,8 @@ def test_three_branch_arguments_are_checked_on_the_host():
 
     def part(nbytes):
         return (nbytes + 255) // 256 * 256
-    expect = (4 * part(2 * m * D * 4) + part(2 * m * 3 * 4) + 2 * part(2 * N * D * 4))
+    expect = (4 * part(2 * m * D * 4) + part(2 * m * 3 * 4) + 2 * part(2 * N * D * 4)
+              + 2 * part(2 * N * 4))            # the two branches' log-sum-exps
     assert M.mosaic_bsa_three_branch_workspace_bytes(p, 2, 2) == expect
     assert M.mosaic_bsa_three_branch_workspace_bytes(p, 3, 2) == 0      # 4 x 8 tiles
     assert M.mosaic_bsa_three_branch_workspace_bytes(good(n_select=0), 1, 1) == 0

@@ -494,3 +494,31 @@ def test_three_branch_paper_stage2_layer_reduced_batch(G, oracle):
     assert np.array_equal(sel, sel_ref)
     err = np.abs(got - ref).max()
     assert err <= 2e-2, f"bf16 max-abs error {err}"
+
+
+@pytest.mark.parametrize("dtype,B,heads,kv_heads,H,W,bh,bw,D,n,lh,lw", [
+    ("fp32", 1, 2, 0, 32, 64, 8, 8, 32, 4, 2, 2),     # general kernels
+    ("fp32", 2, 4, 2, 12, 18, 6, 6, 32, 6, 1, 3),     # n = m, b = 36, grouped heads
+    ("bf16", 2, 4, 0, 32, 64, 8, 8, 64, 4, 2, 4),     # head dim 64 matrix-core kernels
+    ("bf16", 1, 4, 1, 32, 64, 8, 8, 64, 1, 1, 1),     # n = 1, local block = the tile itself
+    ("bf16", 1, 8, 2, 16, 256, 1, 128, 64, 5, 2, 2),  # block-contiguous 128-token blocks, grouped
+    ("bf16", 2, 2, 0, 32, 64, 8, 16, 128, 3, 2, 2),   # head dim 128 matrix-core kernels
+])
+def test_three_branch_backward(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n, lh, lw):
+    """Gradients of the three-branch form with the selection held fixed,
+    against the oracle's reverse-mode gradients of the written-out definition."""
+    cfg = shape_ns(B, heads, H, W, bh, bw, D, n, dtype, kv_heads=kv_heads)
+    hk = kv_heads or heads
+    rng = np.random.default_rng(8500 + H + D + n)
+    q, dout = (rng.standard_normal((B, heads, H * W, D)).astype(np.float32) for _ in range(2))
+    k, v = (rng.standard_normal((B, hk, H * W, D)).astype(np.float32) for _ in range(2))
+    if dtype == "bf16":
+        q, k, v, dout = (round_to_bf16(x) for x in (q, k, v, dout))
+    gates = rng.uniform(0.0, 1.0, size=(B, heads, H * W, 3)).astype(np.float32)
+    s = oracle.shape_of(cfg, own_is_candidate=True)
+    out, sel, dq, dk, dv, dg = G.gpu_three_branch_fwd_bwd(cfg, q, k, v, gates, dout, lh, lw)
+    rq, rk, rv, rg, _ = oracle.bwd_three_branch(s, q, k, v, gates, dout, sel, lh, lw)
+    assert np.array_equal(sel, oracle.select_all(s, q, oracle.expand_kv(k, heads)))
+    check_grads(cfg, (dq, dk, dv), (rq, rk, rv))
+    tol = (2e-2 if dtype == "bf16" else 1e-4) * max(1.0, np.abs(rg).max())
+    assert np.abs(dg - rg).max() <= tol
