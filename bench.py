@@ -274,6 +274,28 @@ def main():
             "tokens_per_s": tokens / (tb_ms * 1e-3),
             "effective_tflops": tb_flops / (tb_ms * 1e-3) / 1e12,
         }
+        if args.with_bwd:
+            nb = M.mosaic_bsa_three_branch_bwd_workspace_bytes(prm, lh, lw)
+            ws_tb = torch.empty(nb, dtype=torch.uint8, device=dev)
+            gen = torch.Generator(device=dev).manual_seed(16429005)
+            dout3 = torch.randn(q.shape, generator=gen, device=dev,
+                                dtype=torch.float32).to(q.dtype)
+            dq3, dk3, dv3 = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+            dg3 = torch.empty_like(gates)
+
+            def bwd3():
+                M.mosaic_bsa_bwd_three_branch(prm, lh, lw, q, k, v, gates, dout3, idx, ws_t,
+                                              dq3, dk3, dv3, dg3, ws_tb)
+            bwd3()
+            torch.cuda.synchronize()
+            reps = max(2, args.steps // 4)
+            e0.record()
+            for _ in range(reps):
+                bwd3()
+            e1.record()
+            torch.cuda.synchronize()
+            result["three_branch"]["bwd_ms"] = e0.elapsed_time(e1) / reps
+            del ws_tb, dout3, dq3, dk3, dv3, dg3
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(problem, cfg)
     print(json.dumps(result))
