@@ -528,71 +528,58 @@ int coarse_bwd_group_size(int m, int D)
     return 0;
 }
 
-// One workgroup per (key/value slice, 8 consecutive key blocks).  Thread =
-// (channel quad, partition of the query blocks); columns j0..j0+7 of a and ds
-// are 32 contiguous bytes per query block.
+// One lane per key block j (a wavefront covers 64 consecutive ones of one
+// key/value slice): it walks the query blocks i in ascending order, reading
+// column j of a and ds (lanes read consecutive addresses) and adding
+// a_ij * dobar_i and ds_ij * qbar_i into its D-channel accumulators; the rows
+// dobar_i and qbar_i are the same for the whole wavefront.
 template <int D>
 __global__ __launch_bounds__(256) void coarse_bwd_cols_kernel(
     const float* __restrict__ qbar, const float* __restrict__ dobar,
     const float* __restrict__ a_in, const float* __restrict__ ds_in, float* __restrict__ dkbar,
-    float* __restrict__ dvbar, Geom g)
+    float* __restrict__ dvbar, Geom g, int64_t waves)
 {
-    constexpr int CG = D / 4, IP = 256 / CG, C = kCoarseRows;
-    __shared__ __attribute__((aligned(16))) float red_s[2 * IP * C * D];
     const int m = g.n_blocks;
-    const int groups = (m + C - 1) / C;
-    const int64_t kv = blockIdx.x / groups;           // key/value slice
-    const int j0 = (int)(blockIdx.x - kv * groups) * C;
-    const int cols = min(C, m - j0);
+    const int chunks = (m + 63) / 64;
+    // (made uniform for the compiler: the rows below then come in through scalar loads)
+    const int64_t wave_id =
+        (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (wave_id >= waves) return;                     // whole wavefront; no barriers below
+    const int64_t kv = wave_id / chunks;              // key/value slice
     const int64_t kv_heads = g.heads / g.kv_group;
+    const int j = (int)(wave_id - kv * chunks) * 64 + (int)(threadIdx.x & 63);
+    const int jc = j < m ? j : m - 1;                 // clamped column of an idle lane
     const int64_t bh_first = (kv / kv_heads) * g.heads + (kv % kv_heads) * g.kv_group;
-    const int cg = threadIdx.x % CG, ip = threadIdx.x / CG;
 
-    float4 acc_k[C], acc_v[C];
+    float acc_k[D], acc_v[D];
 #pragma unroll
-    for (int c = 0; c < C; ++c) {
-        acc_k[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        acc_v[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    }
-    // query heads of the group in ascending order, query blocks ascending inside a partition
+    for (int d = 0; d < D; ++d) { acc_k[d] = 0.0f; acc_v[d] = 0.0f; }
+    // query heads of the group in ascending order, query blocks ascending
     for (int gq = 0; gq < g.kv_group; ++gq) {
         const int64_t bh = bh_first + gq;
-        for (int i = ip; i < m; i += IP) {
-            const float4 q4 = *(const float4*)(qbar + (bh * m + i) * D + 4 * cg);
-            const float4 d4 = *(const float4*)(dobar + (bh * m + i) * D + 4 * cg);
-            const float* a_row = a_in + (bh * m + i) * (int64_t)m + j0;
-            const float* s_row = ds_in + (bh * m + i) * (int64_t)m + j0;
+        const float* a_col = a_in + bh * m * (int64_t)m + jc;
+        const float* s_col = ds_in + bh * m * (int64_t)m + jc;
+        const float* q_rows = qbar + bh * m * D;
+        const float* d_rows = dobar + bh * m * D;
+        for (int i = 0; i < m; ++i) {
+            const float a = a_col[(int64_t)i * m], ds = s_col[(int64_t)i * m];
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                if (c < cols) {
-                    const float a = a_row[c], ds = s_row[c];
-                    acc_v[c].x = fmaf(a, d4.x, acc_v[c].x);
-                    acc_v[c].y = fmaf(a, d4.y, acc_v[c].y);
-                    acc_v[c].z = fmaf(a, d4.z, acc_v[c].z);
-                    acc_v[c].w = fmaf(a, d4.w, acc_v[c].w);
-                    acc_k[c].x = fmaf(ds, q4.x, acc_k[c].x);
-                    acc_k[c].y = fmaf(ds, q4.y, acc_k[c].y);
-                    acc_k[c].z = fmaf(ds, q4.z, acc_k[c].z);
-                    acc_k[c].w = fmaf(ds, q4.w, acc_k[c].w);
-                }
+            for (int d = 0; d < D; ++d) {
+                acc_v[d] = fmaf(a, d_rows[i * D + d], acc_v[d]);
+                acc_k[d] = fmaf(ds, q_rows[i * D + d], acc_k[d]);
             }
         }
     }
+    if (j < m) {
+        float* dk_row = dkbar + (kv * m + j) * D;
+        float* dv_row = dvbar + (kv * m + j) * D;
 #pragma unroll
-    for (int c = 0; c < C; ++c) {
-        *(float4*)(red_s + ((ip * C + c) * D) + 4 * cg) = acc_k[c];
-        *(float4*)(red_s + IP * C * D + ((ip * C + c) * D) + 4 * cg) = acc_v[c];
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < cols * D; e += blockDim.x) {
-        const int c = e / D, d = e - c * D;
-        float sk = 0.0f, sv = 0.0f;
-        for (int p = 0; p < IP; ++p) {
-            sk += red_s[(p * C + c) * D + d];
-            sv += red_s[IP * C * D + (p * C + c) * D + d];
+        for (int d = 0; d < D; d += 4) {
+            *(float4*)(dk_row + d) = make_float4(acc_k[d] * g.scale, acc_k[d + 1] * g.scale,
+                                                 acc_k[d + 2] * g.scale, acc_k[d + 3] * g.scale);
+            *(float4*)(dv_row + d) =
+                make_float4(acc_v[d], acc_v[d + 1], acc_v[d + 2], acc_v[d + 3]);
         }
-        dkbar[(kv * m + j0 + c) * D + d] = sk * g.scale;
-        dvbar[(kv * m + j0 + c) * D + d] = sv;
     }
 }
 
@@ -677,9 +664,9 @@ static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, cons
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t BKV = BH / g.kv_group;
-    hipLaunchKernelGGL((coarse_bwd_cols_kernel<D>),
-                       dim3((unsigned)(BKV * ((m + kCoarseRows - 1) / kCoarseRows))), dim3(256), 0,
-                       stream, qbar, dobar, a_mat, ds_mat, dkbar, dvbar, g);
+    const int64_t waves = BKV * ((m + 63) / 64);
+    hipLaunchKernelGGL((coarse_bwd_cols_kernel<D>), dim3((unsigned)((waves + 3) / 4)), dim3(256),
+                       0, stream, qbar, dobar, a_mat, ds_mat, dkbar, dvbar, g, waves);
     return hipGetLastError();
 }
 
