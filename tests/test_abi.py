@@ -142,3 +142,38 @@ def test_three_branch_arguments_are_checked_on_the_host():
     with pytest.raises(M.BsaError) as e:
         M.mosaic_bsa_fwd_three_branch(p, 2, 2, *args, stream=0, workspace_bytes=expect - 1)
     assert e.value.code == -6
+
+
+def test_three_branch_backward_arguments_are_checked_on_the_host():
+    p = good(n_select=4)
+    fake = 0x1000
+    nbytes = M.mosaic_bsa_three_branch_bwd_workspace_bytes(p, 2, 2)
+    assert nbytes > 0 and nbytes % 256 == 0
+    assert M.mosaic_bsa_three_branch_bwd_workspace_bytes(p, 3, 2) == 0
+    assert M.mosaic_bsa_three_branch_bwd_workspace_bytes(good(n_select=0), 2, 2) == 0
+    args = [fake] * 11
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_bwd_three_branch(p, 2, 2, *args, fake, stream=0, workspace_bytes=nbytes - 1)
+    assert e.value.code == -6
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_bwd_three_branch(p, 2, 5, *args, fake, stream=0, workspace_bytes=nbytes)
+    assert e.value.code == -2
+    bad = list(args)
+    bad[6] = None                       # the forward's workspace
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_bwd_three_branch(p, 2, 2, *bad, fake, stream=0, workspace_bytes=nbytes)
+    assert e.value.code == -1
+    bad = list(args)
+    bad[7] = fake + 8                   # dq misaligned
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_bwd_three_branch(p, 2, 2, *bad, fake, stream=0, workspace_bytes=nbytes)
+    assert e.value.code == -7
+
+
+def test_probe_arguments_are_checked_on_the_host():
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_probe_mfma(None, 4, 10, stream=0)
+    assert e.value.code == -1
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_probe_mfma(0x1000, 0, 10, stream=0)
+    assert e.value.code == -2
