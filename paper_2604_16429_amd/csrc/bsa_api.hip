@@ -60,6 +60,7 @@ int check_params(const mosaic_bsa_params* p, Checked* out, bool own_is_candidate
     g.scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
     g.kv_group = p->heads / kv_heads;
     g.list_only = 0;
+    g.add_dq = g.add_dk = g.add_dv = nullptr;
     g.own_is_candidate = own_is_candidate ? 1 : 0;
     return MOSAIC_BSA_OK;
 }
@@ -307,7 +308,7 @@ namespace {
 
 // Workspace of the three-branch backward: 256-byte aligned parts in this order.
 struct ThreeBranchBwdLayout {
-    size_t attn, do_fg, do_l, dq_l, dk_l, dv_l, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, total;
+    size_t attn, do_fg, do_l, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, total;
 };
 
 ThreeBranchBwdLayout three_branch_bwd_layout(const Checked& c)
@@ -323,9 +324,6 @@ ThreeBranchBwdLayout three_branch_bwd_layout(const Checked& c)
     w.attn = take(bwd_workspace(c));                 // scratch of the attention backward kernels
     w.do_fg = take((size_t)c.BH * N * c.D * esz);
     w.do_l = take((size_t)c.BH * N * c.D * esz);
-    w.dq_l = take((size_t)c.BH * N * c.D * esz);
-    w.dk_l = take((size_t)c.BKV * N * c.D * esz);
-    w.dv_l = take((size_t)c.BKV * N * c.D * esz);
     w.dobar = take((size_t)c.BH * m * c.D * 4);
     w.a_mat = take((size_t)c.BH * m * m * 4);
     w.ds_mat = take((size_t)c.BH * m * m * 4);
@@ -392,25 +390,21 @@ extern "C" int mosaic_bsa_bwd_three_branch(const mosaic_bsa_params* params, int3
     if (backward(c, g_fg, q, k, v, fw + f.o_fg, (const float*)(fw + f.lse_fg), ws + w.do_fg,
                  sel_idx, dq, dk, dv, ws + w.attn, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
-    // local branch -> scratch
-    bsa::Geom g_l = c.g;
-    g_l.n_select = local_tiles - 1;
-    if (backward(c, g_l, q, k, v, fw + f.o_l, (const float*)(fw + f.lse_l), ws + w.do_l, lists,
-                 ws + w.dq_l, ws + w.dk_l, ws + w.dv_l, ws + w.attn, stream) != hipSuccess)
-        return MOSAIC_BSA_ERR_LAUNCH;
     // coarse branch on the pooled tensors
     if (bsa::launch_coarse_bwd(qbar, kbar, vbar, dobar, (float*)(ws + w.a_mat),
                                (float*)(ws + w.ds_mat), (float*)(ws + w.dqbar),
                                (float*)(ws + w.dkbar), (float*)(ws + w.dvbar), c.g, c.D, c.BH,
                                stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
-    // dx = selection branch + local branch + the block's pooled gradient / b
-    if (bsa::launch_add_branches(c.is_bf16, dq, ws + w.dq_l, (const float*)(ws + w.dqbar), c.g,
-                                 c.D, c.BH, stream) != hipSuccess ||
-        bsa::launch_add_branches(c.is_bf16, dk, ws + w.dk_l, (const float*)(ws + w.dkbar), c.g,
-                                 c.D, c.BKV, stream) != hipSuccess ||
-        bsa::launch_add_branches(c.is_bf16, dv, ws + w.dv_l, (const float*)(ws + w.dvbar), c.g,
-                                 c.D, c.BKV, stream) != hipSuccess)
+    // local branch, added in place together with the block's pooled gradient / b:
+    // dx = selection branch + local branch + coarse branch
+    bsa::Geom g_l = c.g;
+    g_l.n_select = local_tiles - 1;
+    g_l.add_dq = (const float*)(ws + w.dqbar);
+    g_l.add_dk = (const float*)(ws + w.dkbar);
+    g_l.add_dv = (const float*)(ws + w.dvbar);
+    if (backward(c, g_l, q, k, v, fw + f.o_l, (const float*)(fw + f.lse_l), ws + w.do_l, lists,
+                 dq, dk, dv, ws + w.attn, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     return MOSAIC_BSA_OK;
 }

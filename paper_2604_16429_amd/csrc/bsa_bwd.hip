@@ -153,11 +153,15 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(
     }
 
     if (valid) {
+        const float inv_b = 1.0f / (float)b;
+        const float* extra =
+            g.add_dq ? g.add_dq + (bh_idx * g.n_blocks + i) * D + quarter * CPT : nullptr;
 #pragma unroll
         for (int d = 0; d < CPT; d += 4)
-            store4(dq + base + tok_q * D + quarter * CPT + d,
-                   make_float4(acc[d] * g.scale, acc[d + 1] * g.scale, acc[d + 2] * g.scale,
-                               acc[d + 3] * g.scale));
+            store4_or_add(dq + base + tok_q * D + quarter * CPT + d,
+                          make_float4(acc[d] * g.scale, acc[d + 1] * g.scale, acc[d + 2] * g.scale,
+                                      acc[d + 3] * g.scale),
+                          extra ? extra + d : nullptr, inv_b);
     }
 }
 
@@ -268,13 +272,19 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(
     }
 
     if (valid) {
+        const float inv_b = 1.0f / (float)b;
+        const int64_t pooled_row = (kv_idx * g.n_blocks + j) * D + quarter * CPT;
+        const float* extra_k = g.add_dk ? g.add_dk + pooled_row : nullptr;
+        const float* extra_v = g.add_dv ? g.add_dv + pooled_row : nullptr;
 #pragma unroll
         for (int d = 0; d < CPT; d += 4) {
-            store4(dk + base + tok_k * D + quarter * CPT + d,
-                   make_float4(acck[d] * g.scale, acck[d + 1] * g.scale, acck[d + 2] * g.scale,
-                               acck[d + 3] * g.scale));
-            store4(dv + base + tok_k * D + quarter * CPT + d,
-                   make_float4(accv[d], accv[d + 1], accv[d + 2], accv[d + 3]));
+            store4_or_add(dk + base + tok_k * D + quarter * CPT + d,
+                          make_float4(acck[d] * g.scale, acck[d + 1] * g.scale,
+                                      acck[d + 2] * g.scale, acck[d + 3] * g.scale),
+                          extra_k ? extra_k + d : nullptr, inv_b);
+            store4_or_add(dv + base + tok_k * D + quarter * CPT + d,
+                          make_float4(accv[d], accv[d + 1], accv[d + 2], accv[d + 3]),
+                          extra_v ? extra_v + d : nullptr, inv_b);
         }
     }
 }

@@ -142,16 +142,29 @@ __device__ __forceinline__ void pack_tile(const f32x16& x, bf16x8 (&b)[2])
 }
 
 // Store one accumulator tile (rows = channels 32 dt .., this lane's column =
-// one token row) scaled by f: 4 consecutive channels per 8-byte store.
+// one token row) scaled by f: 4 consecutive channels per 8-byte store.  With
+// `extra` (fp32 row of D channels) the tile is added to what the row holds,
+// together with extra * inv_b.
 __device__ __forceinline__ void store_tile(uint16_t* row_ptr, int dt, int half, const f32x16& a,
-                                           float f)
+                                           float f, const float* extra = nullptr,
+                                           float inv_b = 0.0f)
 {
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
         const int d = 32 * dt + 8 * r4 + 4 * half;
+        float x0 = a[4 * r4] * f, x1 = a[4 * r4 + 1] * f, x2 = a[4 * r4 + 2] * f,
+              x3 = a[4 * r4 + 3] * f;
+        if (extra) {
+            const uint2 old = *(const uint2*)(row_ptr + d);
+            const float4 e = *(const float4*)(extra + d);
+            x0 += __uint_as_float(old.x << 16) + e.x * inv_b;
+            x1 += __uint_as_float(old.x & 0xffff0000u) + e.y * inv_b;
+            x2 += __uint_as_float(old.y << 16) + e.z * inv_b;
+            x3 += __uint_as_float(old.y & 0xffff0000u) + e.w * inv_b;
+        }
         uint2 w;
-        w.x = pack_bf16(a[4 * r4] * f, a[4 * r4 + 1] * f);
-        w.y = pack_bf16(a[4 * r4 + 2] * f, a[4 * r4 + 3] * f);
+        w.x = pack_bf16(x0, x1);
+        w.y = pack_bf16(x2, x3);
         *(uint2*)(row_ptr + d) = w;
     }
 }
@@ -288,8 +301,10 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
     }
 
     uint16_t* row_ptr = dq + base + q_tok * D;
+    const float inv_b = 1.0f / (float)g.block_tokens;
+    const float* extra = g.add_dq ? g.add_dq + (bh_idx * g.n_blocks + i) * D : nullptr;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) store_tile(row_ptr, dt, half, acc[dt], g.scale);
+    for (int dt = 0; dt < DT; ++dt) store_tile(row_ptr, dt, half, acc[dt], g.scale, extra, inv_b);
 }
 
 // ---------------------------------------------------------------------------
@@ -328,11 +343,12 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
     // workgroup -> (key/value slice, key block), slices dealt to the 8 XCDs
     // whole; the query slices that share the key/value slice are consecutive
     int j;
-    int64_t base, bh_first;
+    int64_t base, bh_first, kv_unit;
     {
         uint32_t unit, r;
         map_unit(blockIdx.x, (uint32_t)m, n_units, unit, r);
         j = (int)r;
+        kv_unit = unit;
         base = (int64_t)unit * g.n_tokens * D;
         const uint32_t kv_heads = (uint32_t)(g.heads / g.kv_group);
         const uint32_t e = unit / kv_heads, a = unit - e * kv_heads;
@@ -489,10 +505,16 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
     }
     }
 
+    const float inv_b = 1.0f / (float)g.block_tokens;
+    const int64_t pooled_row = (kv_unit * m + j) * D;
+    const float* extra_k = g.add_dk ? g.add_dk + pooled_row : nullptr;
+    const float* extra_v = g.add_dv ? g.add_dv + pooled_row : nullptr;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-        if constexpr (DO_DK) store_tile(dk + base + k_tok * D, dt, half, acck[dt], g.scale);
-        if constexpr (DO_DV) store_tile(dv + base + k_tok * D, dt, half, accv[dt], 1.0f);
+        if constexpr (DO_DK)
+            store_tile(dk + base + k_tok * D, dt, half, acck[dt], g.scale, extra_k, inv_b);
+        if constexpr (DO_DV)
+            store_tile(dv + base + k_tok * D, dt, half, accv[dt], 1.0f, extra_v, inv_b);
     }
 }
 

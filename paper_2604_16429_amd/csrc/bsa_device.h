@@ -24,7 +24,18 @@ struct Geom {
     int32_t list_only;    // forward: 1 = attend exactly the n listed blocks (n >= 1), 0 = block i
                           // itself, then the n listed blocks
     int32_t own_is_candidate;  // selection: 1 = rank all m key blocks, 0 = all but block i
+    // Backward: when not null, a gradient is ADDED to what dq / dk / dv hold,
+    // together with row [slice, block of the token] of these fp32 [slices, m, D]
+    // tensors divided by b (the three-branch form: the local branch adds to the
+    // selection branch's result and brings the coarse branch's share along).
+    const float* add_dq;
+    const float* add_dk;
+    const float* add_dv;
 };
+
+// out = v, or in accumulate mode (extra != null) out = old + v + extra[0..3] * inv_b
+template <typename T>
+__device__ __forceinline__ void store4_or_add(T* p, float4 v, const float* extra, float inv_b);
 
 // [N, D] slice of K and V that the query slice bh = batch * heads + head
 // attends to (grouped query attention: consecutive query heads share one).
@@ -130,6 +141,18 @@ __device__ __forceinline__ void store4(uint16_t* p, float4 v)
     r.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
     r.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
     *(uint2*)p = r;
+}
+
+template <typename T>
+__device__ __forceinline__ void store4_or_add(T* p, float4 v, const float* extra, float inv_b)
+{
+    if (extra) {
+        const float4 old = load4(p);
+        const float4 e = *(const float4*)extra;
+        v = make_float4(old.x + v.x + e.x * inv_b, old.y + v.y + e.y * inv_b,
+                        old.z + v.z + e.z * inv_b, old.w + v.w + e.w * inv_b);
+    }
+    store4(p, v);
 }
 
 }  // namespace bsa

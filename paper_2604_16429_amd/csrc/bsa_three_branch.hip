@@ -304,9 +304,9 @@ hipError_t launch_combine(bool is_bf16, const float* obar, const void* o_fg, con
 //                        sum_i a_ij dobar_i and dkbar_j = scale * sum_i ds_ij
 //                        qbar_i, summed over the query heads of the group in
 //                        ascending order.
-//   add_branches_kernel  dx += dx_local + (pooled gradient of the token's
-//                        block) / b: the mean pooling hands every token of a
-//                        block the same share.
+// The pooled gradients reach the tokens in the local branch's attention
+// backward, whose stores add (pooled gradient of the token's block) / b: the
+// mean pooling hands every token of a block the same share.
 // ---------------------------------------------------------------------------
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void branch_grads_kernel(
@@ -583,35 +583,6 @@ __global__ __launch_bounds__(256) void coarse_bwd_cols_kernel(
     }
 }
 
-// dx[row] += dx_other[row] + pooled[slice, block of the token] / b
-template <typename T, int VEC>
-__global__ __launch_bounds__(256) void add_branches_kernel(T* __restrict__ dx,
-                                                           const T* __restrict__ dx_other,
-                                                           const float* __restrict__ pooled,
-                                                           Geom g, int D, int64_t total)
-{
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= total) return;
-    const int per_row = D / VEC;
-    const int64_t row = e / per_row;
-    const int ch = (int)(e - row * per_row) * VEC;
-    const int64_t slice = row / g.n_tokens;
-    const int64_t tok = row - slice * g.n_tokens;
-    const int gr = (int)(tok / g.grid_w), gc = (int)(tok - (int64_t)gr * g.grid_w);
-    const int beta = (gr / g.block_h) * g.blocks_per_row + gc / g.block_w;
-    const float inv_b = 1.0f / (float)g.block_tokens;
-    const float* pb = pooled + (slice * g.n_blocks + beta) * D + ch;
-#pragma unroll
-    for (int v = 0; v < VEC; v += 4) {
-        const float4 a = load4(dx + row * D + ch + v);
-        const float4 o = load4(dx_other + row * D + ch + v);
-        const float4 p = *(const float4*)(pb + v);
-        store4(dx + row * D + ch + v,
-               make_float4(a.x + o.x + p.x * inv_b, a.y + o.y + p.y * inv_b,
-                           a.z + o.z + p.z * inv_b, a.w + o.w + p.w * inv_b));
-    }
-}
-
 hipError_t launch_branch_grads(bool is_bf16, const float* obar, const void* o_fg, const void* o_l,
                                const float* gates, const void* dout, void* do_fg, void* do_l,
                                float* dgates, float* dobar, const Geom& g, int D, int64_t BH,
@@ -681,23 +652,6 @@ hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* 
     case 128: return launch_coarse_bwd_t<128>(qbar, kbar, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
     }
     return hipErrorInvalidValue;
-}
-
-hipError_t launch_add_branches(bool is_bf16, void* dx, const void* dx_other, const float* pooled,
-                               const Geom& g, int D, int64_t slices, hipStream_t stream)
-{
-    if (is_bf16) {
-        const int64_t total = slices * g.n_tokens * (D / 8);
-        hipLaunchKernelGGL((add_branches_kernel<uint16_t, 8>),
-                           dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                           (uint16_t*)dx, (const uint16_t*)dx_other, pooled, g, D, total);
-    } else {
-        const int64_t total = slices * g.n_tokens * (D / 4);
-        hipLaunchKernelGGL((add_branches_kernel<float, 4>), dim3((unsigned)((total + 255) / 256)),
-                           dim3(256), 0, stream, (float*)dx, (const float*)dx_other, pooled, g, D,
-                           total);
-    }
-    return hipGetLastError();
 }
 
 }  // namespace bsa
