@@ -522,3 +522,49 @@ def test_three_branch_backward(G, oracle, dtype, B, heads, kv_heads, H, W, bh, b
     check_grads(cfg, (dq, dk, dv), (rq, rk, rv))
     tol = (2e-2 if dtype == "bf16" else 1e-4) * max(1.0, np.abs(rg).max())
     assert np.abs(dg - rg).max() <= tol
+
+
+def test_select_and_forward_replay_from_a_hip_graph(G, oracle):
+    """The entry points allocate nothing and launch on the caller's stream, so a
+    select + forward step can be captured once and replayed (the small
+    configurations are launch-bound).  Every replay, with eager work and
+    synchronisations in between, must reproduce the eager result bit for bit."""
+    import paper_2604_16429_amd as M
+    from paper_2604_16429_amd import binding
+    cfg = shape_ns(1, 4, 32, 64, 8, 8, 64, 4, "bf16")
+    prm = G.params_of(cfg)
+    qs = [G.to_dev(round_to_bf16(rand_qkv(cfg, 40 + t)[0]), cfg) for t in range(3)]
+    ks = [G.to_dev(round_to_bf16(rand_qkv(cfg, 50 + t)[1]), cfg) for t in range(3)]
+    vs = [G.to_dev(round_to_bf16(rand_qkv(cfg, 60 + t)[2]), cfg) for t in range(3)]
+    q, k, v = (torch.empty_like(qs[0]) for _ in range(3))
+    idx = torch.empty((1, 4, cfg.n_blocks, 4), dtype=torch.int32, device="cuda")
+    out = torch.empty_like(q)
+    lse = torch.empty((1, 4, cfg.n_tokens), dtype=torch.float32, device="cuda")
+    ws = torch.empty(M.mosaic_bsa_workspace_bytes(prm, binding.OP_SELECT), dtype=torch.uint8,
+                     device="cuda")
+
+    def step():
+        M.mosaic_bsa_select(prm, q, k, idx, ws)
+        M.mosaic_bsa_fwd(prm, q, k, v, idx, out, lse)
+
+    eager = []
+    for t in range(3):                       # eager results (also the warm-up before capture)
+        q.copy_(qs[t]); k.copy_(ks[t]); v.copy_(vs[t])
+        step()
+        torch.cuda.synchronize()
+        eager.append((idx.clone(), out.clone(), lse.clone()))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(2):
+        for t in range(3):
+            q.copy_(qs[t]); k.copy_(ks[t]); v.copy_(vs[t])
+            out.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(idx, eager[t][0])
+            assert torch.equal(out, eager[t][1]) and torch.equal(lse, eager[t][2])
