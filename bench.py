@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--three-branch", type=int, nargs=2, metavar=("LOCAL_H", "LOCAL_W"),
                     help="also time the three-branch forward (coarse + selection + local "
                          "branches, gated sum) with large local blocks of LOCAL_H x LOCAL_W tiles")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="also capture one step in a HIP graph and time its replays (the small "
+                         "configurations are launch-bound)")
     ap.add_argument("--with-bwd", action="store_true",
                     help="also run the backward (selection held fixed) after the timed steps "
                          "and report its time; it is not part of a step")
@@ -224,6 +227,22 @@ def main():
             "traffic": traffic,
         },
     }
+    if args.hip_graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        result["hip_graph_ms_per_step"] = (time.perf_counter() - tg0) * 1e3 / args.steps
     if args.with_bwd:
         if problem.dout is not None:
             dout = up(problem.dout)
