@@ -54,9 +54,10 @@ __device__ __forceinline__ float wave_sum(float v)
 //            of its key partition (a row of vbar is read by D/4 adjacent
 //            lanes, 16 bytes each) and accumulates weight * value for all G
 //            rows in registers.
-//   phase 4: the partitions' partial rows are summed through LDS in fixed
-//            order and scaled by 1 / row sum.
-// LDS: G*D (pooled queries) + G*m (scores) + (1024/D)*G*D (partials) + G floats.
+//   phase 4: the partitions' partial rows are summed, first inside each
+//            wavefront (lanes with the same channel quad), then through LDS,
+//            in fixed order, and scaled by 1 / row sum.
+// LDS: G*D (pooled queries) + G*m (scores) + 4*G*D (partials) + G floats.
 template <int D>
 __global__ __launch_bounds__(256) void coarse_kernel(const float* __restrict__ qbar,
                                                      const float* __restrict__ kbar,
@@ -68,8 +69,8 @@ __global__ __launch_bounds__(256) void coarse_kernel(const float* __restrict__ q
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int m = g.n_blocks;
     float* q_s = (float*)smem;                       // [G][D]
-    float* red_s = q_s + G * D;                      // [JP][G][D]
-    float* inv_s = red_s + JP * G * D;               // [8]
+    float* red_s = q_s + G * D;                      // [4 wavefronts][G][D]
+    float* inv_s = red_s + 4 * G * D;                // [8]
     float* sc_s = inv_s + kCoarseRows;               // [G][m]
 
     const int groups = (m + G - 1) / G;
@@ -147,23 +148,33 @@ __global__ __launch_bounds__(256) void coarse_kernel(const float* __restrict__ q
             }
         }
     }
+    // ---- phase 4: the 64 / CG partitions of a wavefront hold the same channel
+    // quad CG lanes apart: butterfly sums, then one partial row per wavefront
 #pragma unroll
     for (int r = 0; r < kCoarseRows; ++r)
-        if (r < rows) *(float4*)(red_s + ((jp * G + r) * D) + 4 * cg) = acc[r];
+        for (int off = CG; off < 64; off <<= 1) {
+            acc[r].x += __shfl_xor(acc[r].x, off);
+            acc[r].y += __shfl_xor(acc[r].y, off);
+            acc[r].z += __shfl_xor(acc[r].z, off);
+            acc[r].w += __shfl_xor(acc[r].w, off);
+        }
+    if (lane < CG) {
+#pragma unroll
+        for (int r = 0; r < kCoarseRows; ++r)
+            if (r < rows) *(float4*)(red_s + ((wave * G + r) * D) + 4 * cg) = acc[r];
+    }
     __syncthreads();
-
-    // ---- phase 4: sum the partitions in ascending order
     for (int e = threadIdx.x; e < rows * D; e += blockDim.x) {
         const int r = e / D, d = e - r * D;
         float sum = 0.0f;
-        for (int p = 0; p < JP; ++p) sum += red_s[(p * G + r) * D + d];
+        for (int p = 0; p < 4; ++p) sum += red_s[(p * G + r) * D + d];
         obar[(bh_idx * m + i0 + r) * D + d] = sum * inv_s[r];
     }
 }
 
 static size_t coarse_lds_bytes(int G, int m, int D)
 {
-    return ((size_t)G * D + (size_t)(1024 / D) * G * D + kCoarseRows + (size_t)G * m) * 4;
+    return ((size_t)G * D + (size_t)4 * G * D + kCoarseRows + (size_t)G * m) * 4;
 }
 
 int coarse_group_size(int m, int D)
@@ -391,8 +402,8 @@ __global__ __launch_bounds__(256) void gated_block_sum_kernel(const T* __restric
 }
 
 // Same workgroup shape as coarse_kernel (G <= 8 query blocks of one slice).
-// LDS: 2*G*D (pooled queries, dobar rows) + (1024/D)*G*D (partials) +
-// 2*G*m (weights, ds) floats.
+// LDS: 2*G*D (pooled queries, dobar rows) + 4*G*D (partials) + 2*G*m
+// (weights, ds) floats.
 template <int D>
 __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
     const float* __restrict__ qbar, const float* __restrict__ kbar,
@@ -404,8 +415,8 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
     const int m = g.n_blocks;
     float* q_s = (float*)smem;                       // [G][D]
     float* do_s = q_s + G * D;                       // [G][D]
-    float* red_s = do_s + G * D;                     // [JP][G][D]
-    float* sc_s = red_s + JP * G * D;                // [G][m]: scores -> weights a
+    float* red_s = do_s + G * D;                     // [4 wavefronts][G][D]
+    float* sc_s = red_s + 4 * G * D;                 // [G][m]: scores -> weights a
     float* da_s = sc_s + G * m;                      // [G][m]: da -> ds
 
     const int groups = (m + G - 1) / G;
@@ -504,21 +515,32 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
             }
         }
     }
+    // the partitions of a wavefront hold the same channel quad CG lanes apart
 #pragma unroll
     for (int r = 0; r < kCoarseRows; ++r)
-        if (r < rows) *(float4*)(red_s + ((jp * G + r) * D) + 4 * cg) = acc[r];
+        for (int off = CG; off < 64; off <<= 1) {
+            acc[r].x += __shfl_xor(acc[r].x, off);
+            acc[r].y += __shfl_xor(acc[r].y, off);
+            acc[r].z += __shfl_xor(acc[r].z, off);
+            acc[r].w += __shfl_xor(acc[r].w, off);
+        }
+    if (lane < CG) {
+#pragma unroll
+        for (int r = 0; r < kCoarseRows; ++r)
+            if (r < rows) *(float4*)(red_s + ((wave * G + r) * D) + 4 * cg) = acc[r];
+    }
     __syncthreads();
     for (int e = threadIdx.x; e < rows * D; e += blockDim.x) {
         const int r = e / D, d = e - r * D;
         float sum = 0.0f;
-        for (int p = 0; p < JP; ++p) sum += red_s[(p * G + r) * D + d];
+        for (int p = 0; p < 4; ++p) sum += red_s[(p * G + r) * D + d];
         dqbar[(row0 + r) * D + d] = sum * g.scale;
     }
 }
 
 static size_t coarse_bwd_lds_bytes(int G, int m, int D)
 {
-    return ((size_t)2 * G * D + (size_t)(1024 / D) * G * D + (size_t)2 * G * m) * 4;
+    return ((size_t)2 * G * D + (size_t)4 * G * D + (size_t)2 * G * m) * 4;
 }
 
 int coarse_bwd_group_size(int m, int D)
