@@ -568,3 +568,20 @@ def test_select_and_forward_replay_from_a_hip_graph(G, oracle):
             torch.cuda.synchronize()
             assert torch.equal(idx, eager[t][0])
             assert torch.equal(out, eager[t][1]) and torch.equal(lse, eager[t][2])
+
+
+def test_three_branch_results_are_run_to_run_identical(G, oracle):
+    """Every sum in the three-branch forward and backward has a fixed order
+    (no floating-point atomics): two runs agree bit for bit, grouped heads
+    included."""
+    cfg = shape_ns(2, 4, 32, 64, 8, 8, 64, 5, "bf16", kv_heads=2)
+    rng = np.random.default_rng(4242)
+    q, dout = (round_to_bf16(rng.standard_normal((2, 4, 2048, 64)).astype(np.float32))
+               for _ in range(2))
+    k, v = (round_to_bf16(rng.standard_normal((2, 2, 2048, 64)).astype(np.float32))
+            for _ in range(2))
+    gates = rng.uniform(0.0, 1.0, size=(2, 4, 2048, 3)).astype(np.float32)
+    first = G.gpu_three_branch_fwd_bwd(cfg, q, k, v, gates, dout, 2, 2)
+    second = G.gpu_three_branch_fwd_bwd(cfg, q, k, v, gates, dout, 2, 2)
+    for a, b in zip(first, second):
+        assert np.array_equal(a, b)
