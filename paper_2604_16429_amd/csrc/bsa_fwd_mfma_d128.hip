@@ -472,22 +472,29 @@ __device__ __forceinline__ void fwd_mfma_q32_body(
     }
 }
 
-// head dim 128: query blocks of 128 tokens, two wavefronts per SIMD
-__global__ __launch_bounds__(256, 2) void fwd_mfma_d128_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-    const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
-    uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, uint32_t n_units)
-{
-    fwd_mfma_q32_body<128, 4>(q, k, v, sel_idx, out, lse, g, n_units);
-}
+// head dim 128: query blocks of 128 tokens (the gradient configuration), 64 and
+// 256 tokens as workgroups of 4, 2 and 8 wavefronts; two wavefronts per SIMD
+#define BSA_FWD_D128_KERNEL(NAME, NW_)                                                            \
+    __global__ __launch_bounds__(64 * NW_, 2) void NAME(                                          \
+        const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,                           \
+        const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,                      \
+        uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, uint32_t n_units)            \
+    {                                                                                             \
+        fwd_mfma_q32_body<128, NW_>(q, k, v, sel_idx, out, lse, g, n_units);                      \
+    }
+BSA_FWD_D128_KERNEL(fwd_mfma_d128_kernel, 4)
+BSA_FWD_D128_KERNEL(fwd_mfma_d128_w2_kernel, 2)
+BSA_FWD_D128_KERNEL(fwd_mfma_d128_w8_kernel, 8)
+#undef BSA_FWD_D128_KERNEL
 
 bool fwd_mfma_d128_supported(bool is_bf16, const Geom& g, int D)
 {
-    // query block = 4 wavefronts x 32 rows; 64-key sub-tiles of whole tile rows
-    // or 64-token runs of a row (the tile width is a power of two) whose 4-token
-    // load slabs are contiguous (the
-    // width is at least 4); buffer offsets inside a slice are 32-bit
-    return is_bf16 && D == 128 && g.block_tokens == 128 &&
+    // query block = 2, 4 or 8 wavefronts x 32 rows; 64-key sub-tiles of whole
+    // tile rows or 64-token runs of a row (the tile width is a power of two)
+    // whose 4-token load slabs are contiguous (the width is at least 4); buffer
+    // offsets inside a slice are 32-bit
+    const int b = g.block_tokens;
+    return is_bf16 && D == 128 && (b == 64 || b == 128 || b == 256) &&
            (g.block_w & (g.block_w - 1)) == 0 && g.block_w >= 4 && g.n_tokens * D * 2 < ((int64_t)1 << 31);
 }
 
@@ -496,7 +503,10 @@ hipError_t launch_fwd_mfma_d128(const void* q, const void* k, const void* v,
                                 int64_t BH, hipStream_t stream)
 {
     dim3 grid((unsigned)(BH * g.n_blocks));
-    fwd_mfma_d128_kernel<<<grid, dim3(256), 0, stream>>>(
+    const int nw = g.block_tokens / 32;
+    auto kernel = nw == 4 ? fwd_mfma_d128_kernel
+                  : nw == 2 ? fwd_mfma_d128_w2_kernel : fwd_mfma_d128_w8_kernel;
+    kernel<<<grid, dim3(64 * nw), 0, stream>>>(
         (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, sel_idx, (uint16_t*)out, lse, g,
         (uint32_t)(BH / g.kv_group));
     return hipGetLastError();

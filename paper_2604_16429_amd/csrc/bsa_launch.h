@@ -36,8 +36,8 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, const in
                            void* out, float* lse, const Geom& g, int D, int64_t BH,
                            hipStream_t stream);
 
-// bf16 MFMA forward for head dim 128 (query blocks of 128 tokens, one workgroup
-// of four wavefronts each, K/V tiles shared through LDS).
+// bf16 MFMA forward for head dim 128 (query blocks of 64, 128 or 256 tokens, one
+// workgroup of 2, 4 or 8 wavefronts each, K/V tiles shared through LDS).
 bool fwd_mfma_d128_supported(bool is_bf16, const Geom& g, int D);
 hipError_t launch_fwd_mfma_d128(const void* q, const void* k, const void* v,
                                 const int32_t* sel_idx, void* out, float* lse, const Geom& g,

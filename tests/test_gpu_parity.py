@@ -107,9 +107,14 @@ def test_mfma_tile_shapes(G, oracle, H, W, bh, bw, n):
     (64, 32, 32, 4, 5),      # 4-token load slabs, the narrowest supported tile
     (8, 64, 8, 16, 1),       # one row of tiles
     (16, 256, 1, 128, 4),    # block-contiguous layout: a block is 128 consecutive tokens
+    (32, 64, 8, 8, 5),       # 64-token tiles: workgroups of two wavefronts
+    (32, 32, 16, 4, 3),      # 64-token tiles, the narrowest supported width
+    (64, 64, 16, 16, 4),     # 256-token tiles: workgroups of eight wavefronts
+    (8, 512, 1, 256, 0),     # block-contiguous 256-token blocks, block-diagonal
 ])
 def test_mfma_d128_tile_shapes(G, oracle, H, W, bh, bw, n):
-    """bf16, D = 128, tiles of 128 tokens (four-wavefront matrix-core kernel)."""
+    """bf16, D = 128, tiles of 64, 128 or 256 tokens (matrix-core kernel with 32
+    query rows per wavefront)."""
     cfg = shape_ns(2, 2, H, W, bh, bw, 128, n, "bf16")
     q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 700 + bh + bw))
     full_parity(G, oracle, cfg, q, k, v)
