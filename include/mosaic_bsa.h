@@ -225,6 +225,23 @@ int mosaic_bsa_bwd_three_branch(const mosaic_bsa_params *params, int32_t local_h
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Checker for selections that were not produced by mosaic_bsa_select: the
+ * attention entry points trust sel_idx (an out-of-range index is undefined
+ * behaviour), so a caller that builds its own lists can have them counted
+ * first.  Not part of the hot path.
+ *   sel_idx             in   device, int32 [B, heads, m, n]
+ *   own_block_allowed        0: the contract of mosaic_bsa_fwd / _bwd (a row
+ *                            never names its own block, n <= m - 1); non-zero:
+ *                            the three-branch form's lists (it may, n <= m)
+ *   n_bad               out  device, one int32: the number of entries that are
+ *                            outside [0, m), repeat an earlier entry of their
+ *                            row, or name the own block when that is not
+ *                            allowed; 0 means the lists are safe to use.
+ */
+int mosaic_bsa_check_selection(const mosaic_bsa_params *params, const int32_t *sel_idx,
+                               int32_t own_block_allowed, int32_t *n_bad, void *hip_stream);
+
+/*
  * Measurement aid, not part of the attention path: a register-resident bf16
  * matrix-core loop (no loads, no LDS, no vector work) whose rate is the most
  * the matrix pipe sustains on the device at hand.  `workgroups` workgroups of

@@ -101,6 +101,8 @@ def load_library() -> ctypes.CDLL:
         lib.mosaic_bsa_bwd_three_branch.restype = i32
         lib.mosaic_bsa_bwd_three_branch.argtypes = (
             [pp, ctypes.c_int32, ctypes.c_int32] + [vp] * 12 + [sz, vp])
+        lib.mosaic_bsa_check_selection.restype = i32
+        lib.mosaic_bsa_check_selection.argtypes = [pp, vp, ctypes.c_int32, vp, vp]
         lib.mosaic_bsa_probe_mfma.restype = i32
         lib.mosaic_bsa_probe_mfma.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
         lib.mosaic_bsa_strerror.restype = ctypes.c_char_p
@@ -212,3 +214,11 @@ def mosaic_bsa_bwd_three_branch(params: Params, local_h: int, local_w: int, q, k
         ctypes.byref(cp), int(local_h), int(local_w), _ptr(q), _ptr(k), _ptr(v), _ptr(gates),
         _ptr(dout), _ptr(sel_idx), _ptr(fwd_workspace), _ptr(dq), _ptr(dk), _ptr(dv),
         _ptr(dgates), _ptr(workspace), wb, _stream(stream)))
+
+
+def mosaic_bsa_check_selection(params: Params, sel_idx, own_block_allowed: bool, n_bad,
+                               stream=None) -> None:
+    cp = params.c_struct()
+    _check(load_library().mosaic_bsa_check_selection(
+        ctypes.byref(cp), _ptr(sel_idx), 1 if own_block_allowed else 0, _ptr(n_bad),
+        _stream(stream)))

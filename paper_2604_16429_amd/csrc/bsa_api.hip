@@ -409,6 +409,19 @@ extern "C" int mosaic_bsa_bwd_three_branch(const mosaic_bsa_params* params, int3
     return MOSAIC_BSA_OK;
 }
 
+extern "C" int mosaic_bsa_check_selection(const mosaic_bsa_params* params,
+                                          const int32_t* sel_idx, int32_t own_block_allowed,
+                                          int32_t* n_bad, void* hip_stream)
+{
+    Checked c;
+    if (int rc = check_params(params, &c, own_block_allowed != 0)) return rc;
+    if (!n_bad || (c.g.n_select > 0 && !sel_idx)) return MOSAIC_BSA_ERR_NULL;
+    return bsa::launch_check_selection(sel_idx, n_bad, c.g, own_block_allowed != 0, c.BH,
+                                       (hipStream_t)hip_stream) == hipSuccess
+               ? MOSAIC_BSA_OK
+               : MOSAIC_BSA_ERR_LAUNCH;
+}
+
 extern "C" int mosaic_bsa_probe_mfma(float* sink, int32_t workgroups, int32_t iters,
                                      void* hip_stream)
 {

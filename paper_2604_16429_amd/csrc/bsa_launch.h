@@ -15,6 +15,12 @@ int select_group_size(int m, int D);
 hipError_t launch_pool(bool is_bf16, const void* q, const void* k, float* qbar, float* kbar,
                        const Geom& g, int D, int64_t BH, hipStream_t stream);
 
+// Counts, into *n_bad (device), the entries of sel_idx that the attention
+// kernels must not be given: out of [0, m), repeated within a row, or (unless
+// own_ok) the row's own block.
+hipError_t launch_check_selection(const int32_t* sel_idx, int32_t* n_bad, const Geom& g,
+                                  bool own_ok, int64_t BH, hipStream_t stream);
+
 // Pooled means of one key/value-shaped tensor (slices = batch * kv_heads).
 hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom& g, int D,
                            int64_t slices, hipStream_t stream);

@@ -385,6 +385,47 @@ __global__ __launch_bounds__(256) void topn_kernel(const uint32_t* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------
+// Checker for caller-made selections (the attention kernels trust sel_idx):
+// one thread per row counts the entries that are out of range, repeat an
+// earlier entry of the row or, unless own_ok, name the row's own block.
+// ---------------------------------------------------------------------------
+__global__ void zero_counter_kernel(int32_t* counter) { *counter = 0; }
+
+__global__ __launch_bounds__(256) void check_selection_kernel(const int32_t* __restrict__ sel_idx,
+                                                              int32_t* __restrict__ n_bad, Geom g,
+                                                              int own_ok, int64_t rows)
+{
+    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int bad = 0;
+    if (row < rows) {
+        const int n = g.n_select, m = g.n_blocks;
+        const int own = (int)(row % m);
+        const int32_t* r = sel_idx + row * n;
+        for (int a = 0; a < n; ++a) {
+            const int32_t x = r[a];
+            bool is_bad = x < 0 || x >= m || (!own_ok && x == own);
+            for (int c = 0; c < a && !is_bad; ++c) is_bad = r[c] == x;
+            bad += is_bad ? 1 : 0;
+        }
+    }
+    // one integer atomic per wavefront with something to report
+    for (int off = 32; off >= 1; off >>= 1) bad += __shfl_xor(bad, off);
+    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(n_bad, bad);
+}
+
+hipError_t launch_check_selection(const int32_t* sel_idx, int32_t* n_bad, const Geom& g,
+                                  bool own_ok, int64_t BH, hipStream_t stream)
+{
+    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, stream, n_bad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || g.n_select == 0) return e;
+    const int64_t rows = BH * g.n_blocks;
+    hipLaunchKernelGGL(check_selection_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0,
+                       stream, sel_idx, n_bad, g, own_ok ? 1 : 0, rows);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------
 static constexpr size_t kSelectLdsBudget = 144 * 1024;

@@ -177,3 +177,13 @@ def test_probe_arguments_are_checked_on_the_host():
     with pytest.raises(M.BsaError) as e:
         M.mosaic_bsa_probe_mfma(0x1000, 0, 10, stream=0)
     assert e.value.code == -2
+
+
+def test_selection_checker_arguments_are_checked_on_the_host():
+    p = good()
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_check_selection(p, 0x1000, False, None, stream=0)
+    assert e.value.code == -1
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_check_selection(good(n_select=32), 0x1000, False, 0x1000, stream=0)
+    assert e.value.code == -3                           # n = m only with the own block allowed

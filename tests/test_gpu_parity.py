@@ -590,3 +590,23 @@ def test_three_branch_results_are_run_to_run_identical(G, oracle):
     second = G.gpu_three_branch_fwd_bwd(cfg, q, k, v, gates, dout, 2, 2)
     for a, b in zip(first, second):
         assert np.array_equal(a, b)
+
+
+def test_selection_checker_counts_what_the_kernels_must_not_get(G, oracle):
+    import paper_2604_16429_amd as M
+    cfg = shape_ns(2, 3, 32, 64, 8, 8, 64, 5, "bf16")
+    prm = G.params_of(cfg)
+    q, k, _ = (round_to_bf16(x) for x in rand_qkv(cfg, 321))
+    idx = torch.from_numpy(G.gpu_select(cfg, q, k)).to("cuda")
+    n_bad = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    M.mosaic_bsa_check_selection(prm, idx, False, n_bad)
+    assert int(n_bad.item()) == 0                       # what select emits is clean
+    bad = idx.clone()
+    bad[0, 0, 3, 2] = cfg.n_blocks                      # out of range
+    bad[1, 2, 7, 0] = -1                                # negative
+    bad[0, 1, 5, 4] = bad[0, 1, 5, 1]                   # repeats an earlier entry
+    bad[1, 0, 9, 3] = 9                                 # the row's own block
+    M.mosaic_bsa_check_selection(prm, bad, False, n_bad)
+    assert int(n_bad.item()) == 4
+    M.mosaic_bsa_check_selection(prm, bad, True, n_bad)     # own block allowed: three left
+    assert int(n_bad.item()) == 3
