@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE, each scaled by the same counter on a plain copy kernel of known
 # size: 2048 and 1024 bytes per count); profiles/fwd_mfma_b64_d64_config3.md.
 # None for workloads that have not been measured.
-MEASURED_FWD_TRAFFIC_BYTES = {3: 17.92e9 + 1.47e9}
+MEASURED_FWD_TRAFFIC_BYTES = {3: 17.96e9 + 1.47e9}
 
 
 def parse_args():
