@@ -134,6 +134,21 @@ __device__ __forceinline__ float4 load4(const uint16_t* p)
                        __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
 }
 
+// The same with the non-temporal hint (data that is read once).
+__device__ __forceinline__ float4 load4_stream(const float* p)
+{
+    typedef float f4v __attribute__((ext_vector_type(4)));
+    const f4v r = __builtin_nontemporal_load((const f4v*)p);
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ float4 load4_stream(const uint16_t* p)
+{
+    typedef uint32_t u2v __attribute__((ext_vector_type(2)));
+    const u2v r = __builtin_nontemporal_load((const u2v*)p);
+    return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
+                       __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
+}
+
 __device__ __forceinline__ void store4(float* p, float4 v) { *(float4*)p = v; }
 __device__ __forceinline__ void store4(uint16_t* p, float4 v)
 {

@@ -61,7 +61,8 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
         for (int cc = 0; cc < g.block_w; ++cc) {
 #pragma unroll
             for (int e4 = 0; e4 < VEC; e4 += 4) {
-                const float4 v = load4(row + (int64_t)cc * D + e4);
+                // streamed: every byte is used once here, nothing is worth caching
+                const float4 v = load4_stream(row + (int64_t)cc * D + e4);
                 acc[e4 + 0] = acc[e4 + 0] + v.x;
                 acc[e4 + 1] = acc[e4 + 1] + v.y;
                 acc[e4 + 2] = acc[e4 + 2] + v.z;
