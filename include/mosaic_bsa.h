@@ -21,6 +21,14 @@
  *     selected blocks (fine-grained attention equation).
  *   - mosaic_bsa_bwd: gradients of that attention with the selection held
  *     fixed (Appendix "Block-sparse attention implementation", kernel design).
+ *   - mosaic_bsa_fwd_three_branch / mosaic_bsa_bwd_three_branch: the
+ *     subsection's own output form, three branches (coarse-grained attention
+ *     over the pooled blocks, selection, local attention inside large blocks)
+ *     with a softmax each, summed with gate values that the caller supplies
+ *     (aggregation equation of the Native Sparse Attention subsection), and
+ *     its gradients.
+ *   - mosaic_bsa_check_selection, mosaic_bsa_probe_mfma: a checker for
+ *     caller-made selections and a measurement aid; neither is on the hot path.
  *
  * Conventions common to all entry points
  *   Pointers  q, k, v, out, dout, dq, dk, dv, sel_idx, lse and the workspace
