@@ -89,35 +89,48 @@ __device__ __forceinline__ uint32_t rank_key(float s)
     return max((u & 0x80000000u) ? ~u : (u | 0x80000000u), 1u);
 }
 
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp(uint32_t v)
-{
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
-}
-
 // Wave-wide reductions over all 64 lanes (all lanes must be active); the
 // result is wave-uniform.  Four DPP butterfly steps inside each row of 16
-// lanes, then the four row results are combined through scalar registers.
+// lanes, then two row broadcasts (lane 15 of a row into the next row, lane 31
+// into rows 2 and 3; lanes of the other rows are not written) leave the result
+// in lane 63.  Written as one instruction per step: the compiler emits three
+// for a row broadcast.  A DPP operand must not be read in the two issue slots
+// after it was written, hence the s_nop between the steps.
+#define BSA_WAVE_REDUCE(OP, V)                                                              \
+    asm volatile("s_nop 1\n\t"                                                             \
+                 OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t" \
+                 OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t" \
+                 OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"      \
+                 OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"           \
+                 OP " %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\ts_nop 1\n\t"         \
+                 OP " %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\ts_nop 1"              \
+                 : "+v"(V))
+
 __device__ __forceinline__ uint32_t wave_umax(uint32_t v)
 {
-    v = max(v, dpp<0xB1>(v));    // quad_perm [1,0,3,2]
-    v = max(v, dpp<0x4E>(v));    // quad_perm [2,3,0,1]
-    v = max(v, dpp<0x141>(v));   // row_half_mirror
-    v = max(v, dpp<0x140>(v));   // row_mirror
-    const uint32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
-    const uint32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
-    return max(max(a, b), max(c, d));
+    BSA_WAVE_REDUCE("v_max_u32_dpp", v);
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 __device__ __forceinline__ uint32_t wave_umin(uint32_t v)
 {
-    v = min(v, dpp<0xB1>(v));
-    v = min(v, dpp<0x4E>(v));
-    v = min(v, dpp<0x141>(v));
-    v = min(v, dpp<0x140>(v));
-    const uint32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
-    const uint32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
-    return min(min(a, b), min(c, d));
+    BSA_WAVE_REDUCE("v_min_u32_dpp", v);
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+// Descending sort of 8 distinct 64-bit values held in registers (Batcher's
+// odd-even merge network, 19 compare-exchanges).
+__device__ __forceinline__ void sort8_desc(uint64_t (&a)[9])
+{
+#define BSA_CE(i, j) { const uint64_t x = a[i], y = a[j]; const bool sw = y > x; \
+                       a[i] = sw ? y : x; a[j] = sw ? x : y; }
+    BSA_CE(0, 1) BSA_CE(2, 3) BSA_CE(4, 5) BSA_CE(6, 7)
+    BSA_CE(0, 2) BSA_CE(1, 3) BSA_CE(4, 6) BSA_CE(5, 7)
+    BSA_CE(1, 2) BSA_CE(5, 6)
+    BSA_CE(0, 4) BSA_CE(1, 5) BSA_CE(2, 6) BSA_CE(3, 7)
+    BSA_CE(2, 4) BSA_CE(3, 5)
+    BSA_CE(1, 2) BSA_CE(3, 4) BSA_CE(5, 6)
+#undef BSA_CE
 }
 
 // Candidates a lane keeps in registers in the top-n phase (m <= 64 * kSlots).
@@ -134,7 +147,7 @@ constexpr int kSlots = 8;
 //            j == lane (mod 64); a wave-wide max of the scores and then a
 //            wave-wide min of the indices among the lanes holding that max
 //            give the next selected block; only the winner's lane rescans.
-// LDS: G*D floats (pooled queries) + G*m u32 (ranking keys).
+// LDS: G*m u32 (ranking keys).
 template <int D>
 __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ qbar,
                                                      const float* __restrict__ kbar,
@@ -142,8 +155,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
                                                      int G)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float* q_s = (float*)smem;                       // [G][D]
-    uint32_t* key_s = (uint32_t*)(q_s + G * D);      // [G][m]
+    uint32_t* key_s = (uint32_t*)smem;               // [G][m]
 
     const int m = g.n_blocks, n = g.n_select;
     // blockIdx.x = batch*head * groups + group
@@ -154,10 +166,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
     qbar += (bh_idx * m + i0) * D;
     kbar += kv_slice_of(g, bh_idx) * m * D;
 
-    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) q_s[e] = qbar[e];
-    __syncthreads();
-
-    // ---- phase 1: scores
+    // ---- phase 1: scores.  The pooled queries are wave-uniform and are fetched
+    // with scalar loads straight into the fma's scalar operand.
     for (int j = threadIdx.x; j < m; j += blockDim.x) {
         float kr[D];
         const float4* krow = (const float4*)(kbar + (int64_t)j * D);
@@ -168,16 +178,10 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
             kr[4 * d4 + 2] = v.z; kr[4 * d4 + 3] = v.w;
         }
         for (int r = 0; r < rows; ++r) {
-            const float4* qrow = (const float4*)(q_s + r * D);
+            const float* __restrict__ qrow = qbar + r * D;
             float acc = 0.0f;
 #pragma unroll
-            for (int d4 = 0; d4 < D / 4; ++d4) {
-                const float4 qv = qrow[d4];
-                acc = __builtin_fmaf(qv.x, kr[4 * d4 + 0], acc);
-                acc = __builtin_fmaf(qv.y, kr[4 * d4 + 1], acc);
-                acc = __builtin_fmaf(qv.z, kr[4 * d4 + 2], acc);
-                acc = __builtin_fmaf(qv.w, kr[4 * d4 + 3], acc);
-            }
+            for (int d = 0; d < D; ++d) acc = __builtin_fmaf(qrow[d], kr[d], acc);
             key_s[r * m + j] = (j == i0 + r && !g.own_is_candidate) ? 0u : rank_key(acc);
         }
     }
@@ -189,26 +193,25 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
         uint32_t* keys = key_s + r * m;
         int32_t* dst = sel_idx + ((bh_idx * m) + i0 + r) * n;
         if (m <= 64 * kSlots) {
-            // Candidates j == lane (mod 64) live in registers, slot t = j / 64.
-            // Per round: wave-wide max of the lanes' best keys; the winner is
-            // the lane holding it (the smallest block index among them when
-            // several do, which only happens for exactly equal scores); that
-            // lane clears the slot and re-derives its best.
-            uint32_t kreg[kSlots];
+            // Candidates j == lane (mod 64) live in registers as composites
+            // (key << 32 | ~j), which are all distinct and order the
+            // candidates exactly as the ranking does.  Every lane sorts its 8
+            // composites (descending) once; per round: wave-wide max of the
+            // lanes' head keys, the winner is the lane holding it (the
+            // smallest block index among them when several do, which only
+            // happens for exactly equal scores), and that lane moves on to its
+            // next composite.  Lane t % 64 keeps pick t; 64 picks go out in
+            // one store.
+            uint64_t srt[kSlots + 1];
 #pragma unroll
             for (int t = 0; t < kSlots; ++t) {
                 const int j = lane + 64 * t;
-                kreg[t] = j < m ? keys[j] : 0u;
+                srt[t] = ((uint64_t)(j < m ? keys[j] : 0u) << 32) | (uint32_t)~j;
             }
-            auto lane_best = [&](uint32_t& best, uint32_t& best_j) {
-                best = kreg[0]; uint32_t slot = 0;
-#pragma unroll
-                for (int t = 1; t < kSlots; ++t)
-                    if (kreg[t] > best) { best = kreg[t]; slot = (uint32_t)t; }
-                best_j = best ? (uint32_t)lane + 64u * slot : 0xffffffffu;
-            };
-            uint32_t best, best_j;
-            lane_best(best, best_j);
+            srt[kSlots] = 0xffffffffull;                 // key 0: nothing left
+            sort8_desc(srt);
+            uint32_t best = (uint32_t)(srt[0] >> 32), best_j = ~(uint32_t)srt[0], head = 0;
+            uint32_t picks = 0;
             for (int t = 0; t < n; ++t) {
                 const uint32_t top = wave_umax(best);
                 const uint64_t holders = __builtin_amdgcn_ballot_w64(best == top);
@@ -217,13 +220,17 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
                     win = __builtin_amdgcn_readlane(best_j, (int)__builtin_ctzll(holders));
                 else
                     win = wave_umin(best == top ? best_j : 0xffffffffu);
-                if (lane == 0) dst[t] = (int32_t)win;
-                if ((win & 63u) == (uint32_t)lane) {
-                    const uint32_t slot = win >> 6;
-#pragma unroll
-                    for (int u = 0; u < kSlots; ++u)
-                        if (slot == (uint32_t)u) kreg[u] = 0u;
-                    lane_best(best, best_j);
+                const int win_lane = (int)(win & 63u);
+                picks = lane == (t & 63) ? win : picks;
+                const uint32_t next = (uint32_t)__builtin_amdgcn_readlane((int)head, win_lane) + 1u;
+                if (lane == win_lane) {
+                    const uint64_t c = srt[next];        // wave-uniform register index
+                    best = (uint32_t)(c >> 32);
+                    best_j = ~(uint32_t)c;
+                    head = next;
+                }
+                if ((t & 63) == 63 || t == n - 1) {
+                    if (lane <= (t & 63)) dst[(t & ~63) + lane] = (int32_t)picks;
                 }
             }
             continue;
@@ -435,7 +442,7 @@ int select_group_size(int m, int D)
 {
     // largest G in [1, 8] whose LDS footprint fits; 0 if even G = 1 does not
     for (int G = 8; G >= 1; G >>= 1)
-        if ((size_t)G * (D + (size_t)m) * 4 <= kSelectLdsBudget) return G;
+        if ((size_t)G * (size_t)m * 4 <= kSelectLdsBudget) return G;
     return 0;
 }
 
@@ -476,18 +483,19 @@ hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom&
     return hipGetLastError();
 }
 
+static bool two_kernel_path(int m) { return m > 64 * kSlots && m <= 64 * kBigSlots; }
+
 size_t select_scratch_bytes(int m, int64_t BH)
 {
     // the two-kernel path keeps the ranking keys of every row in global memory
-    if (m <= 64 * kSlots || m > 64 * kBigSlots) return 0;
-    return (size_t)BH * (size_t)m * (size_t)m * 4;
+    return two_kernel_path(m) ? (size_t)BH * (size_t)m * (size_t)m * 4 : 0;
 }
 
 template <int D>
 static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t* sel_idx,
                                   uint32_t* keys, const Geom& g, int64_t BH, hipStream_t stream)
 {
-    if (select_scratch_bytes(g.n_blocks, BH) != 0) {
+    if (two_kernel_path(g.n_blocks)) {
         const int m = g.n_blocks;
         const int64_t wgs = BH * ((m + kScoreRows - 1) / kScoreRows) * ((m + 255) / 256);
         if (!keys || wgs >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
@@ -501,18 +509,7 @@ static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t*
         return hipGetLastError();
     }
     const int G = select_group_size(g.n_blocks, D);
-    const size_t lds = (size_t)G * (D + (size_t)g.n_blocks) * 4;
-    // the attribute is per device; setting it twice (two host threads racing) is harmless
-    static bool attr_set[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute((const void*)select_kernel<D>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)kSelectLdsBudget);
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
+    const size_t lds = (size_t)G * (size_t)g.n_blocks * 4;
     dim3 grid((unsigned)(BH * ((g.n_blocks + G - 1) / G)));
     hipLaunchKernelGGL((select_kernel<D>), grid, dim3(256), lds, stream, qbar, kbar, sel_idx, g,
                        G);
