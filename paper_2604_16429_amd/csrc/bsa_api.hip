@@ -116,6 +116,10 @@ extern "C" int mosaic_bsa_select(const mosaic_bsa_params* params, const void* q,
     float* qbar = (float*)workspace;
     float* kbar = (float*)((char*)workspace + pooled_bytes(c));
     void* scratch = (char*)workspace + 2 * pooled_bytes(c);
+    if (c.g.n_select > 0 && bsa::pool_select_overlaps(c.g.n_blocks))
+        return bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, sel_idx, c.g, c.D, c.BH,
+                                       stream) == hipSuccess ? MOSAIC_BSA_OK
+                                                             : MOSAIC_BSA_ERR_LAUNCH;
     if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     if (c.g.n_select == 0) return MOSAIC_BSA_OK;
@@ -237,14 +241,20 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
     void* o_fg = ws + w.o_fg;
     void* o_l = ws + w.o_l;
 
-    // compression: pooled q, k, v
-    if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess ||
-        bsa::launch_pool_one(c.is_bf16, v, vbar, c.g, c.D, c.BKV, stream) != hipSuccess)
+    // compression (pooled q, k, v), the coarse branch, and the ranking it shares
+    // with the selection branch
+    if (bsa::pool_select_overlaps(c.g.n_blocks)) {
+        if (bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, sel_idx, c.g, c.D, c.BH,
+                                    stream) != hipSuccess)
+            return MOSAIC_BSA_ERR_LAUNCH;
+    } else if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) !=
+                   hipSuccess ||
+               bsa::launch_select(qbar, kbar, sel_idx, ws + w.keys, c.g, c.D, c.BH, stream) !=
+                   hipSuccess) {
         return MOSAIC_BSA_ERR_LAUNCH;
-    // coarse branch, and the ranking it shares with the selection branch
-    if (bsa::launch_coarse(qbar, kbar, vbar, obar, c.g, c.D, c.BH, stream) != hipSuccess ||
-        bsa::launch_select(qbar, kbar, sel_idx, ws + w.keys, c.g, c.D, c.BH, stream) !=
-            hipSuccess)
+    }
+    if (bsa::launch_pool_one(c.is_bf16, v, vbar, c.g, c.D, c.BKV, stream) != hipSuccess ||
+        bsa::launch_coarse(qbar, kbar, vbar, obar, c.g, c.D, c.BH, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     // selection branch: one softmax over the selected blocks only
     bsa::Geom g_fg = c.g;

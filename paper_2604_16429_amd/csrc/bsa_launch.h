@@ -31,6 +31,14 @@ size_t select_scratch_bytes(int m, int64_t BH);
 hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, void* scratch,
                          const Geom& g, int D, int64_t BH, hipStream_t stream);
 
+// launch_pool + launch_select as one sequence of launches in which the pooling
+// of one part of the batch runs beside the ranking of the part before (only
+// where pool_select_overlaps(m): the ranking that needs no scratch).
+bool pool_select_overlaps(int m);
+hipError_t launch_pool_select(bool is_bf16, const void* q, const void* k, float* qbar,
+                              float* kbar, int32_t* sel_idx, const Geom& g, int D, int64_t BH,
+                              hipStream_t stream);
+
 // Any tile shape / head dim in {32, 64, 128} / dtype; fp32 vector arithmetic.
 hipError_t launch_fwd_generic(bool is_bf16, const void* q, const void* k, const void* v,
                               const int32_t* sel_idx, void* out, float* lse, const Geom& g, int D,

@@ -1,9 +1,12 @@
 // Block selection for block-sparse attention on gfx950:
 //   pool_kernel    mean-pooled block representations of Q and K (pooling
 //                  equation, phi = mean);
-//   select_kernel  block-level scores (block-level attention equation, in its
+//   select_block   block-level scores (block-level attention equation, in its
 //                  rank-equivalent raw dot-product form) and the top-n key
-//                  blocks of every query block (Selection paragraph).
+//                  blocks of every query block (Selection paragraph);
+//   pool_select_kernel  both in one launch: the pooling of one part of the
+//                  batch beside the ranking of the part pooled just before;
+//   scores_kernel, topn_kernel  the ranking for 512 < m <= 4096 blocks.
 //
 // The arithmetic is pinned so that the emitted indices are reproducible bit
 // for bit by a scalar loop: pooled sums are fp32 adds in in-tile row-major
@@ -26,19 +29,19 @@ namespace bsa {
 // 256 in order: consecutive lanes take consecutive channel groups, so every
 // load covers whole 128-byte lines and the tiles of a tile row (bw*D elements
 // each, contiguous in memory) are consumed side by side.
+// `vblock` numbers the workgroups of one pooling pass: (slice, chunk of 256
+// items), the n_q query slices from q_first on, then the n_k key slices from
+// k_first on (fewer under grouped query attention).
 template <typename T, int VEC>
-__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
-                                                   const T* __restrict__ k,
-                                                   float* __restrict__ qbar,
-                                                   float* __restrict__ kbar, Geom g, int D,
-                                                   int64_t BH, int wgs_per_slice)
+__device__ __forceinline__ void pool_block(const T* __restrict__ q, const T* __restrict__ k,
+                                           float* __restrict__ qbar, float* __restrict__ kbar,
+                                           const Geom& g, int D, int64_t q_first, int64_t n_q,
+                                           int64_t k_first, int wgs_per_slice, uint32_t vblock)
 {
-    // blockIdx.x = slice * wgs_per_slice + chunk of 256 items; slices: the BH
-    // query slices, then the key slices (fewer under grouped query attention)
-    const int chunk = blockIdx.x % wgs_per_slice;
-    int64_t bh_idx = blockIdx.x / wgs_per_slice;
-    const bool is_k = bh_idx >= BH;
-    if (is_k) bh_idx -= BH;
+    const int chunk = (int)(vblock % (uint32_t)wgs_per_slice);
+    int64_t bh_idx = vblock / (uint32_t)wgs_per_slice;
+    const bool is_k = bh_idx >= n_q;
+    bh_idx = is_k ? bh_idx - n_q + k_first : bh_idx + q_first;
     const T* __restrict__ x = is_k ? k : q;
     float* __restrict__ xbar = is_k ? kbar : qbar;
     const int groups = D / VEC;
@@ -75,6 +78,16 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
     for (int e4 = 0; e4 < VEC; e4 += 4)
         store4(dst + e4, make_float4(acc[e4] * inv_b, acc[e4 + 1] * inv_b,
                                      acc[e4 + 2] * inv_b, acc[e4 + 3] * inv_b));
+}
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
+                                                   const T* __restrict__ k,
+                                                   float* __restrict__ qbar,
+                                                   float* __restrict__ kbar, Geom g, int D,
+                                                   int64_t BH, int wgs_per_slice)
+{
+    pool_block<T, VEC>(q, k, qbar, kbar, g, D, 0, BH, 0, wgs_per_slice, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -140,28 +153,27 @@ constexpr int kSlots = 8;
 // (batch, head).
 //   phase 1: thread t owns key block j = chunk*256 + t, holds kbar_j in
 //            registers and runs the pinned fma chain against each of the G
-//            pooled queries (read from LDS as wave-wide broadcasts); the
+//            pooled queries (wave-uniform: scalar loads, scalar operands); the
 //            ranking keys of all m candidates of each query land in LDS.
 //   phase 2: one wavefront per query block extracts the n best candidates by
-//            repeated arg-max: every lane caches the best of the candidates
-//            j == lane (mod 64); a wave-wide max of the scores and then a
-//            wave-wide min of the indices among the lanes holding that max
-//            give the next selected block; only the winner's lane rescans.
+//            repeated arg-max over the lanes' best remaining candidates
+//            (j == lane mod 64): a wave-wide max of the scores, then, only if
+//            several lanes hold it, a wave-wide min of their block indices.
 // LDS: G*m u32 (ranking keys).
 template <int D>
-__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ qbar,
-                                                     const float* __restrict__ kbar,
-                                                     int32_t* __restrict__ sel_idx, Geom g,
-                                                     int G)
+__device__ __forceinline__ void select_block(const float* __restrict__ qbar,
+                                             const float* __restrict__ kbar,
+                                             int32_t* __restrict__ sel_idx, const Geom& g, int G,
+                                             uint32_t vblock)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint32_t* key_s = (uint32_t*)smem;               // [G][m]
 
     const int m = g.n_blocks, n = g.n_select;
-    // blockIdx.x = batch*head * groups + group
+    // vblock = batch*head * groups + group
     const int groups = (m + G - 1) / G;
-    const int64_t bh_idx = blockIdx.x / groups;
-    const int i0 = (int)(blockIdx.x - bh_idx * groups) * G;
+    const int64_t bh_idx = vblock / (uint32_t)groups;
+    const int i0 = (int)(vblock - (uint32_t)bh_idx * (uint32_t)groups) * G;
     const int rows = min(G, m - i0);
     qbar += (bh_idx * m + i0) * D;
     kbar += kv_slice_of(g, bh_idx) * m * D;
@@ -254,6 +266,35 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ q
             }
         }
     }
+}
+
+// Pooling of one part of the batch beside the ranking of the part pooled by
+// the launch before: pooling is bound by HBM and leaves the vector ALUs idle,
+// the ranking is bound by the vector ALUs and reads only cached pooled means.
+// The first n_poolers workgroups of the launch pool: they are dispatched
+// first and each walks the part's n_pool_blocks pooling blocks with stride
+// n_poolers, so a fixed number of them stays resident on every CU until the
+// part is pooled (pooling workgroups dealt one block each are short-lived and
+// would be crowded out by the long-lived ranking workgroups).  The other
+// workgroups rank (virtual ids from select_first on).  No workgroup waits for
+// another: what a ranking workgroup reads was written by an earlier launch.
+// The pooled means are passed twice: written through qbar_w / kbar_w (the part
+// being pooled), read through qbar_r / kbar_r (the part being ranked).
+template <typename T, int VEC, int D>
+__global__ __launch_bounds__(256) void pool_select_kernel(
+    const T* __restrict__ q, const T* __restrict__ k, float* __restrict__ qbar_w,
+    float* __restrict__ kbar_w, const float* __restrict__ qbar_r,
+    const float* __restrict__ kbar_r, int32_t* __restrict__ sel_idx, Geom g, int G,
+    int64_t pool_q_first, int64_t pool_n_q, int64_t pool_k_first, int wgs_per_slice,
+    uint32_t n_pool_blocks, uint32_t n_poolers, uint32_t select_first)
+{
+    if (blockIdx.x >= n_poolers) {
+        select_block<D>(qbar_r, kbar_r, sel_idx, g, G, select_first + (blockIdx.x - n_poolers));
+        return;
+    }
+    for (uint32_t v = blockIdx.x; v < n_pool_blocks; v += n_poolers)
+        pool_block<T, VEC>(q, k, qbar_w, kbar_w, g, D, pool_q_first, pool_n_q, pool_k_first,
+                           wgs_per_slice, v);
 }
 
 // ---------------------------------------------------------------------------
@@ -508,12 +549,7 @@ static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t*
                            stream, keys, sel_idx, g, rows_total);
         return hipGetLastError();
     }
-    const int G = select_group_size(g.n_blocks, D);
-    const size_t lds = (size_t)G * (size_t)g.n_blocks * 4;
-    dim3 grid((unsigned)(BH * ((g.n_blocks + G - 1) / G)));
-    hipLaunchKernelGGL((select_kernel<D>), grid, dim3(256), lds, stream, qbar, kbar, sel_idx, g,
-                       G);
-    return hipGetLastError();
+    return hipErrorInvalidValue;     // every other m is ranked by launch_pool_select
 }
 
 hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, void* scratch,
@@ -524,6 +560,91 @@ hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx,
     case 32: return launch_select_t<32>(qbar, kbar, sel_idx, keys, g, BH, stream);
     case 64: return launch_select_t<64>(qbar, kbar, sel_idx, keys, g, BH, stream);
     case 128: return launch_select_t<128>(qbar, kbar, sel_idx, keys, g, BH, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+#ifndef BSA_SELECT_PARTS
+#define BSA_SELECT_PARTS 4
+#endif
+#ifndef BSA_POOLERS
+#define BSA_POOLERS 256
+#endif
+// pooling workgroups that stay resident beside the ranking (one per CU)
+constexpr int64_t kPoolers = BSA_POOLERS;
+
+bool pool_select_overlaps(int m) { return !two_kernel_path(m); }
+
+template <typename T, int VEC, int D>
+static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar, float* kbar,
+                                       int32_t* sel_idx, const Geom& g, int64_t BH,
+                                       hipStream_t stream)
+{
+    const int m = g.n_blocks;
+    const int G = select_group_size(m, D);
+    if (G == 0) return hipErrorInvalidValue;
+    const size_t lds = (size_t)G * (size_t)m * 4;
+    // the attribute is per device; setting it twice (two host threads racing) is harmless
+    static bool attr_set[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        hipError_t e = hipFuncSetAttribute((const void*)pool_select_kernel<T, VEC, D>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kSelectLdsBudget);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    const int64_t BKV = BH / g.kv_group;
+    const int parts = (int)(BKV < BSA_SELECT_PARTS ? BKV : BSA_SELECT_PARTS);
+    const int wgs_per_slice = (m * (D / VEC) + 255) / 256;
+    const int groups = (m + G - 1) / G;
+    // launch t pools part t and ranks part t - 1
+    for (int t = 0; t <= parts; ++t) {
+        int64_t pq0 = 0, pnq = 0, pk0 = 0, n_pool = 0, sel_first = 0, n_sel = 0;
+        if (t < parts) {
+            pk0 = BKV * t / parts;
+            const int64_t pk1 = BKV * (t + 1) / parts;
+            pq0 = pk0 * g.kv_group;
+            pnq = (pk1 - pk0) * g.kv_group;
+            n_pool = (pnq + (pk1 - pk0)) * wgs_per_slice;
+        }
+        if (t >= 1) {
+            const int64_t k0 = BKV * (t - 1) / parts, k1 = BKV * t / parts;
+            sel_first = k0 * g.kv_group * groups;
+            n_sel = (k1 - k0) * g.kv_group * groups;
+        }
+        if (n_pool + n_sel == 0) continue;
+        // alone, the pooling blocks get a workgroup each
+        const int64_t n_poolers = n_sel == 0 ? n_pool : (n_pool < kPoolers ? n_pool : kPoolers);
+        if (n_pool >= ((int64_t)1 << 31) || n_poolers + n_sel >= ((int64_t)1 << 31) ||
+            sel_first + n_sel >= ((int64_t)1 << 32))
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL((pool_select_kernel<T, VEC, D>), dim3((unsigned)(n_poolers + n_sel)),
+                           dim3(256), lds, stream, (const T*)q, (const T*)k, qbar, kbar,
+                           (const float*)qbar, (const float*)kbar, sel_idx, g, G, pq0, pnq, pk0,
+                           wgs_per_slice, (uint32_t)n_pool, (uint32_t)n_poolers,
+                           (uint32_t)sel_first);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_pool_select(bool is_bf16, const void* q, const void* k, float* qbar,
+                              float* kbar, int32_t* sel_idx, const Geom& g, int D, int64_t BH,
+                              hipStream_t stream)
+{
+    switch (D) {
+    case 32:
+        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 32>(q, k, qbar, kbar, sel_idx, g, BH, stream)
+                       : launch_pool_select_t<float, 4, 32>(q, k, qbar, kbar, sel_idx, g, BH, stream);
+    case 64:
+        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 64>(q, k, qbar, kbar, sel_idx, g, BH, stream)
+                       : launch_pool_select_t<float, 4, 64>(q, k, qbar, kbar, sel_idx, g, BH, stream);
+    case 128:
+        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 128>(q, k, qbar, kbar, sel_idx, g, BH, stream)
+                       : launch_pool_select_t<float, 4, 128>(q, k, qbar, kbar, sel_idx, g, BH, stream);
     }
     return hipErrorInvalidValue;
 }
