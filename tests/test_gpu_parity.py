@@ -192,6 +192,43 @@ def test_selection_with_many_blocks(G, oracle, H, W, bh, bw, D, n, dtype):
         assert idx[0, 1, i].tolist() == [j for j in range(cfg.n_blocks) if j != i][:n]
 
 
+@pytest.mark.parametrize("dtype,B,heads,kv_heads,H,W,bh,bw,D,n", [
+    ("fp32", 1, 1, 1, 32, 64, 8, 8, 32, 5),       # one slice: a single part
+    ("fp32", 1, 3, 3, 32, 64, 8, 8, 32, 5),       # three slices: three parts
+    ("bf16", 5, 2, 1, 32, 64, 8, 8, 64, 7),       # 5 key/value slices in 4 parts, 2 query heads each
+    ("bf16", 3, 6, 2, 64, 64, 8, 8, 128, 4),      # 6 key/value slices, head dim 128
+    ("bf16", 5, 8, 8, 120, 240, 8, 8, 64, 16),    # 300 pooling blocks per part: the 256 resident
+                                                  # pooling workgroups take more than one block
+])
+def test_selection_over_parts_of_the_batch(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n):
+    """mosaic_bsa_select pools one part of the batch beside the ranking of the
+    part before: every way the slices fall into parts must give the indices
+    and the pooled means of the one-pass definition, bit for bit."""
+    import paper_2604_16429_amd as M
+    from paper_2604_16429_amd import binding
+    cfg = shape_ns(B, heads, H, W, bh, bw, D, n, dtype, kv_heads=kv_heads)
+    rng = np.random.default_rng(8100 + B + heads + D)
+    q = rng.standard_normal((B, heads, H * W, D)).astype(np.float32)
+    k = rng.standard_normal((B, kv_heads, H * W, D)).astype(np.float32)
+    if dtype == "bf16":
+        q, k = round_to_bf16(q), round_to_bf16(k)
+    s = oracle.shape_of(cfg)
+    prm = G.params_of(cfg)
+    ws = torch.full((M.mosaic_bsa_workspace_bytes(prm, binding.OP_SELECT),), 0xff,
+                    dtype=torch.uint8, device="cuda")
+    idx = torch.full((B, heads, cfg.n_blocks, n), -1, dtype=torch.int32, device="cuda")
+    M.mosaic_bsa_select(prm, G.to_dev(q, cfg), G.to_dev(k, cfg), idx, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), oracle.select_gqa(s, q, k))
+    wsf = ws.view(torch.float32).cpu().numpy()
+    cnt_q = B * heads * cfg.n_blocks * D
+    cnt_k = B * kv_heads * cfg.n_blocks * D
+    k_at = (cnt_q * 4 + 255) // 256 * 256 // 4
+    s_kv = oracle.shape_of(shape_ns(B, kv_heads, H, W, bh, bw, D, n, dtype))
+    assert np.array_equal(wsf[:cnt_q], oracle.pool(s, q).reshape(-1))
+    assert np.array_equal(wsf[k_at:k_at + cnt_k], oracle.pool(s_kv, k).reshape(-1))
+
+
 def test_pooled_means_in_workspace_are_bit_exact(G, oracle):
     import paper_2604_16429_amd as M
     from paper_2604_16429_amd import binding
