@@ -77,7 +77,7 @@ size_t pooled_bytes(const Checked& c)
 
 size_t select_workspace(const Checked& c)
 {
-    return 2 * pooled_bytes(c) + align_up(bsa::select_scratch_bytes(c.g.n_blocks, c.BH));
+    return 2 * pooled_bytes(c) + align_up(bsa::select_scratch_bytes(c.g.n_blocks, c.D, c.BH, c.BKV));
 }
 
 size_t bwd_workspace(const Checked& c)
@@ -117,8 +117,8 @@ extern "C" int mosaic_bsa_select(const mosaic_bsa_params* params, const void* q,
     float* kbar = (float*)((char*)workspace + pooled_bytes(c));
     void* scratch = (char*)workspace + 2 * pooled_bytes(c);
     if (c.g.n_select > 0 && bsa::pool_select_overlaps(c.g.n_blocks))
-        return bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, sel_idx, c.g, c.D, c.BH,
-                                       stream) == hipSuccess ? MOSAIC_BSA_OK
+        return bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, scratch, sel_idx, c.g, c.D,
+                                       c.BH, stream) == hipSuccess ? MOSAIC_BSA_OK
                                                              : MOSAIC_BSA_ERR_LAUNCH;
     if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
@@ -184,7 +184,7 @@ ThreeBranchLayout three_branch_layout(const Checked& c, int local_tiles)
     w.kbar = take((size_t)c.BKV * m * c.D * 4);
     w.vbar = take((size_t)c.BKV * m * c.D * 4);
     w.obar = take((size_t)c.BH * m * c.D * 4);
-    w.keys = take(bsa::select_scratch_bytes(c.g.n_blocks, c.BH));
+    w.keys = take(bsa::select_scratch_bytes(c.g.n_blocks, c.D, c.BH, c.BKV));
     w.lists = take((size_t)c.BH * m * (size_t)(local_tiles - 1) * 4);
     w.o_fg = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
     w.o_l = take((size_t)c.BH * (size_t)c.g.n_tokens * c.D * esz);
@@ -244,8 +244,8 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
     // compression (pooled q, k, v), the coarse branch, and the ranking it shares
     // with the selection branch
     if (bsa::pool_select_overlaps(c.g.n_blocks)) {
-        if (bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, sel_idx, c.g, c.D, c.BH,
-                                    stream) != hipSuccess)
+        if (bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, ws + w.keys, sel_idx, c.g, c.D,
+                                    c.BH, stream) != hipSuccess)
             return MOSAIC_BSA_ERR_LAUNCH;
     } else if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) !=
                    hipSuccess ||

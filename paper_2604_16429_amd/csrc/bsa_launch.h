@@ -25,9 +25,10 @@ hipError_t launch_check_selection(const int32_t* sel_idx, int32_t* n_bad, const 
 hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom& g, int D,
                            int64_t slices, hipStream_t stream);
 
-// `scratch`: device memory of select_scratch_bytes(m, BH) bytes (0 for most
-// shapes: only 512 < m <= 4096 ranks through a global matrix of keys).
-size_t select_scratch_bytes(int m, int64_t BH);
+// `scratch`: device memory of select_scratch_bytes(...) bytes (BKV = batch *
+// kv_heads): for m <= 512 a second copy of the pooled keys, per slice
+// [D/4][m][4], for 512 < m <= 4096 the global matrix of ranking keys, else none.
+size_t select_scratch_bytes(int m, int D, int64_t BH, int64_t BKV);
 hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, void* scratch,
                          const Geom& g, int D, int64_t BH, hipStream_t stream);
 
@@ -36,8 +37,8 @@ hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx,
 // where pool_select_overlaps(m): the ranking that needs no scratch).
 bool pool_select_overlaps(int m);
 hipError_t launch_pool_select(bool is_bf16, const void* q, const void* k, float* qbar,
-                              float* kbar, int32_t* sel_idx, const Geom& g, int D, int64_t BH,
-                              hipStream_t stream);
+                              float* kbar, void* scratch, int32_t* sel_idx, const Geom& g, int D,
+                              int64_t BH, hipStream_t stream);
 
 // Any tile shape / head dim in {32, 64, 128} / dtype; fp32 vector arithmetic.
 hipError_t launch_fwd_generic(bool is_bf16, const void* q, const void* k, const void* v,

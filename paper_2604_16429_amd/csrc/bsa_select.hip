@@ -35,6 +35,7 @@ namespace bsa {
 template <typename T, int VEC>
 __device__ __forceinline__ void pool_block(const T* __restrict__ q, const T* __restrict__ k,
                                            float* __restrict__ qbar, float* __restrict__ kbar,
+                                           float* __restrict__ kbar_il,
                                            const Geom& g, int D, int64_t q_first, int64_t n_q,
                                            int64_t k_first, int wgs_per_slice, uint32_t vblock)
 {
@@ -78,6 +79,16 @@ __device__ __forceinline__ void pool_block(const T* __restrict__ q, const T* __r
     for (int e4 = 0; e4 < VEC; e4 += 4)
         store4(dst + e4, make_float4(acc[e4] * inv_b, acc[e4 + 1] * inv_b,
                                      acc[e4 + 2] * inv_b, acc[e4 + 3] * inv_b));
+    // second copy of the pooled keys for the ranking, per slice [D/4][m][4]: a
+    // wavefront whose lanes hold 64 consecutive key blocks then reads 1 KiB runs
+    if (is_k && kbar_il) {
+        float* il = kbar_il + bh_idx * g.n_blocks * D;
+#pragma unroll
+        for (int e4 = 0; e4 < VEC; e4 += 4)
+            store4(il + ((int64_t)((ch + e4) >> 2) * g.n_blocks + beta) * 4,
+                   make_float4(acc[e4] * inv_b, acc[e4 + 1] * inv_b, acc[e4 + 2] * inv_b,
+                               acc[e4 + 3] * inv_b));
+    }
 }
 
 template <typename T, int VEC>
@@ -87,7 +98,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ q,
                                                    float* __restrict__ kbar, Geom g, int D,
                                                    int64_t BH, int wgs_per_slice)
 {
-    pool_block<T, VEC>(q, k, qbar, kbar, g, D, 0, BH, 0, wgs_per_slice, blockIdx.x);
+    pool_block<T, VEC>(q, k, qbar, kbar, nullptr, g, D, 0, BH, 0, wgs_per_slice, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -151,9 +162,11 @@ constexpr int kSlots = 8;
 
 // One workgroup of 256 threads ranks G consecutive query blocks of one
 // (batch, head).
-//   phase 1: thread t owns key block j = chunk*256 + t, holds kbar_j in
-//            registers and runs the pinned fma chain against each of the G
-//            pooled queries (wave-uniform: scalar loads, scalar operands); the
+//   phase 1: thread t owns key block j = t, t + 256, ..., holds kbar_j in
+//            registers (loaded from the channel-interleaved copy of the pooled
+//            keys where there is one: consecutive lanes then read consecutive
+//            16-byte groups) and runs the pinned fma chain against each of the
+//            G pooled queries (wave-uniform: scalar loads, scalar operands); the
 //            ranking keys of all m candidates of each query land in LDS.
 //   phase 2: one wavefront per query block extracts the n best candidates by
 //            repeated arg-max over the lanes' best remaining candidates
@@ -163,6 +176,7 @@ constexpr int kSlots = 8;
 template <int D>
 __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
                                              const float* __restrict__ kbar,
+                                             const float* __restrict__ kbar_il,
                                              int32_t* __restrict__ sel_idx, const Geom& g, int G,
                                              uint32_t vblock)
 {
@@ -178,14 +192,19 @@ __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
     qbar += (bh_idx * m + i0) * D;
     kbar += kv_slice_of(g, bh_idx) * m * D;
 
+    if (kbar_il) kbar_il += kv_slice_of(g, bh_idx) * m * D;   // per slice [D/4][m][4]
+
     // ---- phase 1: scores.  The pooled queries are wave-uniform and are fetched
     // with scalar loads straight into the fma's scalar operand.
     for (int j = threadIdx.x; j < m; j += blockDim.x) {
         float kr[D];
-        const float4* krow = (const float4*)(kbar + (int64_t)j * D);
+        // the interleaved copy where there is one, else the key block's row
+        const float4* ksrc = kbar_il ? (const float4*)kbar_il + j
+                                     : (const float4*)(kbar + (int64_t)j * D);
+        const int64_t kstep = kbar_il ? (int64_t)m : 1;
 #pragma unroll
         for (int d4 = 0; d4 < D / 4; ++d4) {
-            const float4 v = krow[d4];
+            const float4 v = ksrc[d4 * kstep];
             kr[4 * d4 + 0] = v.x; kr[4 * d4 + 1] = v.y;
             kr[4 * d4 + 2] = v.z; kr[4 * d4 + 3] = v.w;
         }
@@ -278,22 +297,25 @@ __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
 // would be crowded out by the long-lived ranking workgroups).  The other
 // workgroups rank (virtual ids from select_first on).  No workgroup waits for
 // another: what a ranking workgroup reads was written by an earlier launch.
-// The pooled means are passed twice: written through qbar_w / kbar_w (the part
-// being pooled), read through qbar_r / kbar_r (the part being ranked).
+// The pooled means are passed twice: written through qbar_w / kbar_w / kbar_il_w
+// (the part being pooled), read through qbar_r / kbar_r / kbar_il_r (the part
+// being ranked).
 template <typename T, int VEC, int D>
 __global__ __launch_bounds__(256) void pool_select_kernel(
     const T* __restrict__ q, const T* __restrict__ k, float* __restrict__ qbar_w,
-    float* __restrict__ kbar_w, const float* __restrict__ qbar_r,
-    const float* __restrict__ kbar_r, int32_t* __restrict__ sel_idx, Geom g, int G,
+    float* __restrict__ kbar_w, float* __restrict__ kbar_il_w, const float* __restrict__ qbar_r,
+    const float* __restrict__ kbar_r, const float* __restrict__ kbar_il_r,
+    int32_t* __restrict__ sel_idx, Geom g, int G,
     int64_t pool_q_first, int64_t pool_n_q, int64_t pool_k_first, int wgs_per_slice,
     uint32_t n_pool_blocks, uint32_t n_poolers, uint32_t select_first)
 {
     if (blockIdx.x >= n_poolers) {
-        select_block<D>(qbar_r, kbar_r, sel_idx, g, G, select_first + (blockIdx.x - n_poolers));
+        select_block<D>(qbar_r, kbar_r, kbar_il_r, sel_idx, g, G,
+                        select_first + (blockIdx.x - n_poolers));
         return;
     }
     for (uint32_t v = blockIdx.x; v < n_pool_blocks; v += n_poolers)
-        pool_block<T, VEC>(q, k, qbar_w, kbar_w, g, D, pool_q_first, pool_n_q, pool_k_first,
+        pool_block<T, VEC>(q, k, qbar_w, kbar_w, kbar_il_w, g, D, pool_q_first, pool_n_q, pool_k_first,
                            wgs_per_slice, v);
 }
 
@@ -479,11 +501,17 @@ hipError_t launch_check_selection(const int32_t* sel_idx, int32_t* n_bad, const 
 // ---------------------------------------------------------------------------
 static constexpr size_t kSelectLdsBudget = 144 * 1024;
 
+static size_t select_lds_bytes(int G, int m, int D)
+{
+    (void)D;
+    return (size_t)G * (size_t)m * 4;
+}
+
 int select_group_size(int m, int D)
 {
-    // largest G in [1, 8] whose LDS footprint fits; 0 if even G = 1 does not
+    // the largest G in [1, 8] whose LDS footprint fits; 0 if even G = 1 does not
     for (int G = 8; G >= 1; G >>= 1)
-        if ((size_t)G * (size_t)m * 4 <= kSelectLdsBudget) return G;
+        if (select_lds_bytes(G, m, D) <= kSelectLdsBudget) return G;
     return 0;
 }
 
@@ -526,10 +554,12 @@ hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom&
 
 static bool two_kernel_path(int m) { return m > 64 * kSlots && m <= 64 * kBigSlots; }
 
-size_t select_scratch_bytes(int m, int64_t BH)
+size_t select_scratch_bytes(int m, int D, int64_t BH, int64_t BKV)
 {
-    // the two-kernel path keeps the ranking keys of every row in global memory
-    return two_kernel_path(m) ? (size_t)BH * (size_t)m * (size_t)m * 4 : 0;
+    // the two-kernel path keeps the ranking keys of every row in global memory,
+    // the fused ranking of m <= 512 reads a second, interleaved copy of the pooled keys
+    if (two_kernel_path(m)) return (size_t)BH * (size_t)m * (size_t)m * 4;
+    return m <= 64 * kSlots ? (size_t)BKV * (size_t)m * (size_t)D * 4 : 0;
 }
 
 template <int D>
@@ -577,13 +607,13 @@ bool pool_select_overlaps(int m) { return !two_kernel_path(m); }
 
 template <typename T, int VEC, int D>
 static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar, float* kbar,
-                                       int32_t* sel_idx, const Geom& g, int64_t BH,
-                                       hipStream_t stream)
+                                       float* kbar_il, int32_t* sel_idx, const Geom& g,
+                                       int64_t BH, hipStream_t stream)
 {
     const int m = g.n_blocks;
     const int G = select_group_size(m, D);
     if (G == 0) return hipErrorInvalidValue;
-    const size_t lds = (size_t)G * (size_t)m * 4;
+    const size_t lds = select_lds_bytes(G, m, D);
     // the attribute is per device; setting it twice (two host threads racing) is harmless
     static bool attr_set[64] = {};
     int dev = 0;
@@ -621,8 +651,9 @@ static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar
             sel_first + n_sel >= ((int64_t)1 << 32))
             return hipErrorInvalidValue;
         hipLaunchKernelGGL((pool_select_kernel<T, VEC, D>), dim3((unsigned)(n_poolers + n_sel)),
-                           dim3(256), lds, stream, (const T*)q, (const T*)k, qbar, kbar,
-                           (const float*)qbar, (const float*)kbar, sel_idx, g, G, pq0, pnq, pk0,
+                           dim3(256), lds, stream, (const T*)q, (const T*)k, qbar, kbar, kbar_il,
+                           (const float*)qbar, (const float*)kbar, (const float*)kbar_il, sel_idx,
+                           g, G, pq0, pnq, pk0,
                            wgs_per_slice, (uint32_t)n_pool, (uint32_t)n_poolers,
                            (uint32_t)sel_first);
         hipError_t e = hipGetLastError();
@@ -632,19 +663,22 @@ static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar
 }
 
 hipError_t launch_pool_select(bool is_bf16, const void* q, const void* k, float* qbar,
-                              float* kbar, int32_t* sel_idx, const Geom& g, int D, int64_t BH,
-                              hipStream_t stream)
+                              float* kbar, void* scratch, int32_t* sel_idx, const Geom& g, int D,
+                              int64_t BH, hipStream_t stream)
 {
+    // the interleaved copy of the pooled keys (m <= 512)
+    float* il = g.n_blocks <= 64 * kSlots ? (float*)scratch : nullptr;
+    if (g.n_blocks <= 64 * kSlots && !il) return hipErrorInvalidValue;
     switch (D) {
     case 32:
-        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 32>(q, k, qbar, kbar, sel_idx, g, BH, stream)
-                       : launch_pool_select_t<float, 4, 32>(q, k, qbar, kbar, sel_idx, g, BH, stream);
+        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 32>(q, k, qbar, kbar, il, sel_idx, g, BH, stream)
+                       : launch_pool_select_t<float, 4, 32>(q, k, qbar, kbar, il, sel_idx, g, BH, stream);
     case 64:
-        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 64>(q, k, qbar, kbar, sel_idx, g, BH, stream)
-                       : launch_pool_select_t<float, 4, 64>(q, k, qbar, kbar, sel_idx, g, BH, stream);
+        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 64>(q, k, qbar, kbar, il, sel_idx, g, BH, stream)
+                       : launch_pool_select_t<float, 4, 64>(q, k, qbar, kbar, il, sel_idx, g, BH, stream);
     case 128:
-        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 128>(q, k, qbar, kbar, sel_idx, g, BH, stream)
-                       : launch_pool_select_t<float, 4, 128>(q, k, qbar, kbar, sel_idx, g, BH, stream);
+        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 128>(q, k, qbar, kbar, il, sel_idx, g, BH, stream)
+                       : launch_pool_select_t<float, 4, 128>(q, k, qbar, kbar, il, sel_idx, g, BH, stream);
     }
     return hipErrorInvalidValue;
 }

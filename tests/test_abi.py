@@ -44,7 +44,8 @@ def test_workspace_bytes():
     p = good()
     m = 32
     per = (1 * 2 * m * 32 * 4 + 255) // 256 * 256
-    assert M.mosaic_bsa_workspace_bytes(p, binding.OP_SELECT) == 2 * per
+    # pooled q, pooled k, and the ranking's interleaved copy of pooled k
+    assert M.mosaic_bsa_workspace_bytes(p, binding.OP_SELECT) == 3 * per
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_FWD) == 0
     # delta and lse * log2(e), fp32 [B, heads, N] each
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD) == 2 * (1 * 2 * 2048 * 4)
@@ -122,7 +123,7 @@ def test_three_branch_arguments_are_checked_on_the_host():
 
     def part(nbytes):
         return (nbytes + 255) // 256 * 256
-    expect = (4 * part(2 * m * D * 4) + part(2 * m * 3 * 4) + 2 * part(2 * N * D * 4)
+    expect = (5 * part(2 * m * D * 4) + part(2 * m * 3 * 4) + 2 * part(2 * N * D * 4)
               + 2 * part(2 * N * 4))            # the two branches' log-sum-exps
     assert M.mosaic_bsa_three_branch_workspace_bytes(p, 2, 2) == expect
     assert M.mosaic_bsa_three_branch_workspace_bytes(p, 3, 2) == 0      # 4 x 8 tiles
