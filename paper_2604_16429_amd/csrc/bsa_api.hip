@@ -254,7 +254,10 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
         return MOSAIC_BSA_ERR_LAUNCH;
     }
     if (bsa::launch_pool_one(c.is_bf16, v, vbar, c.g, c.D, c.BKV, stream) != hipSuccess ||
-        bsa::launch_coarse(qbar, kbar, vbar, obar, c.g, c.D, c.BH, stream) != hipSuccess)
+        bsa::launch_coarse(qbar, kbar,
+                           bsa::select_interleaves_keys(c.g.n_blocks) ? (const float*)(ws + w.keys)
+                                                                      : nullptr,
+                           vbar, obar, c.g, c.D, c.BH, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     // selection branch: one softmax over the selected blocks only
     bsa::Geom g_fg = c.g;

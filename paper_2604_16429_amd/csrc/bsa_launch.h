@@ -36,6 +36,9 @@ hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx,
 // of one part of the batch runs beside the ranking of the part before (only
 // where pool_select_overlaps(m): the ranking that needs no scratch).
 bool pool_select_overlaps(int m);
+// Whether launch_pool_select leaves the channel-interleaved copy of the pooled
+// keys ([B*kv_heads][D/4][m][4]) at the start of its scratch.
+bool select_interleaves_keys(int m);
 hipError_t launch_pool_select(bool is_bf16, const void* q, const void* k, float* qbar,
                               float* kbar, void* scratch, int32_t* sel_idx, const Geom& g, int D,
                               int64_t BH, hipStream_t stream);
@@ -75,9 +78,12 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
 // Three-branch output: coarse branch (softmax over all pooled key blocks times
 // pooled values, fp32 [B*heads, m, D]), the block lists of the local branch
 // (int32 [B*heads, m, local_h*local_w - 1]) and the gated sum of the branches.
+// kbar_il: the channel-interleaved copy of the pooled keys that
+// launch_pool_select leaves in its scratch for m <= 512, or NULL.
 int coarse_group_size(int m, int D);
-hipError_t launch_coarse(const float* qbar, const float* kbar, const float* vbar, float* obar,
-                         const Geom& g, int D, int64_t BH, hipStream_t stream);
+hipError_t launch_coarse(const float* qbar, const float* kbar, const float* kbar_il,
+                         const float* vbar, float* obar, const Geom& g, int D, int64_t BH,
+                         hipStream_t stream);
 hipError_t launch_local_lists(int32_t* lists, const Geom& g, int local_h, int local_w,
                               int64_t BH, hipStream_t stream);
 hipError_t launch_combine(bool is_bf16, const float* obar, const void* o_fg, const void* o_l,

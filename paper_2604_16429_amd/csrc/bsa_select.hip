@@ -605,6 +605,8 @@ constexpr int64_t kPoolers = BSA_POOLERS;
 
 bool pool_select_overlaps(int m) { return !two_kernel_path(m); }
 
+bool select_interleaves_keys(int m) { return m <= 64 * kSlots; }
+
 template <typename T, int VEC, int D>
 static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar, float* kbar,
                                        float* kbar_il, int32_t* sel_idx, const Geom& g,

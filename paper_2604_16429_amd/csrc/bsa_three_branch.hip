@@ -46,8 +46,8 @@ __device__ __forceinline__ float wave_sum(float v)
 // One workgroup of 256 threads handles G <= 8 consecutive query blocks of one
 // (batch, head).
 //   phase 1: thread t owns key block j = chunk*256 + t, holds kbar_j in
-//            registers and scores it against the G pooled queries (LDS
-//            broadcasts); scaled scores (base-2 domain) land in LDS.
+//            registers and scores it against the G pooled queries (scalar
+//            operands); scaled scores (base-2 domain) land in LDS.
 //   phase 2: one wavefront per query block: row maximum, weights
 //            exp2(s - max) written back in place, 1 / row sum.
 //   phase 3: thread = (channel quad, key partition): walks the pooled values
@@ -57,10 +57,11 @@ __device__ __forceinline__ float wave_sum(float v)
 //   phase 4: the partitions' partial rows are summed, first inside each
 //            wavefront (lanes with the same channel quad), then through LDS,
 //            in fixed order, and scaled by 1 / row sum.
-// LDS: G*D (pooled queries) + G*m (scores) + 4*G*D (partials) + G floats.
+// LDS: G*m (scores) + 4*G*D (partials) + G floats.
 template <int D>
 __global__ __launch_bounds__(256) void coarse_kernel(const float* __restrict__ qbar,
                                                      const float* __restrict__ kbar,
+                                                     const float* __restrict__ kbar_il,
                                                      const float* __restrict__ vbar,
                                                      float* __restrict__ obar, Geom g, int G)
 {
@@ -68,8 +69,7 @@ __global__ __launch_bounds__(256) void coarse_kernel(const float* __restrict__ q
     constexpr int JP = 256 / CG;                     // key partitions
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int m = g.n_blocks;
-    float* q_s = (float*)smem;                       // [G][D]
-    float* red_s = q_s + G * D;                      // [4 wavefronts][G][D]
+    float* red_s = (float*)smem;                     // [4 wavefronts][G][D]
     float* inv_s = red_s + 4 * G * D;                // [8]
     float* sc_s = inv_s + kCoarseRows;               // [G][m]
 
@@ -82,31 +82,28 @@ __global__ __launch_bounds__(256) void coarse_kernel(const float* __restrict__ q
     kbar += kv * m * D;
     vbar += kv * m * D;
 
-    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) q_s[e] = qbar[e];
-    __syncthreads();
+    if (kbar_il) kbar_il += kv * m * D;              // per slice [D/4][m][4]
 
-    // ---- phase 1: scaled scores
+    // ---- phase 1: scaled scores.  The pooled queries are wave-uniform (scalar
+    // loads, scalar operands of the fma); the thread's pooled key comes from the
+    // channel-interleaved copy where there is one (coalesced), else from its row.
     const float c2 = g.scale * kLog2e;
     for (int j = threadIdx.x; j < m; j += blockDim.x) {
         float kr[D];
-        const float4* krow = (const float4*)(kbar + (int64_t)j * D);
+        const float4* ksrc = kbar_il ? (const float4*)kbar_il + j
+                                     : (const float4*)(kbar + (int64_t)j * D);
+        const int64_t kstep = kbar_il ? (int64_t)m : 1;
 #pragma unroll
         for (int d4 = 0; d4 < D / 4; ++d4) {
-            const float4 t = krow[d4];
+            const float4 t = ksrc[d4 * kstep];
             kr[4 * d4 + 0] = t.x; kr[4 * d4 + 1] = t.y;
             kr[4 * d4 + 2] = t.z; kr[4 * d4 + 3] = t.w;
         }
         for (int r = 0; r < rows; ++r) {
-            const float4* qrow = (const float4*)(q_s + r * D);
+            const float* __restrict__ qrow = qbar + r * D;
             float acc = 0.0f;
 #pragma unroll
-            for (int d4 = 0; d4 < D / 4; ++d4) {
-                const float4 qv = qrow[d4];
-                acc = fmaf(qv.x, kr[4 * d4 + 0], acc);
-                acc = fmaf(qv.y, kr[4 * d4 + 1], acc);
-                acc = fmaf(qv.z, kr[4 * d4 + 2], acc);
-                acc = fmaf(qv.w, kr[4 * d4 + 3], acc);
-            }
+            for (int d = 0; d < D; ++d) acc = fmaf(qrow[d], kr[d], acc);
             sc_s[r * m + j] = acc * c2;
         }
     }
@@ -174,7 +171,7 @@ __global__ __launch_bounds__(256) void coarse_kernel(const float* __restrict__ q
 
 static size_t coarse_lds_bytes(int G, int m, int D)
 {
-    return ((size_t)G * D + (size_t)4 * G * D + kCoarseRows + (size_t)G * m) * 4;
+    return ((size_t)4 * G * D + kCoarseRows + (size_t)G * m) * 4;
 }
 
 int coarse_group_size(int m, int D)
@@ -185,8 +182,9 @@ int coarse_group_size(int m, int D)
 }
 
 template <int D>
-static hipError_t launch_coarse_t(const float* qbar, const float* kbar, const float* vbar,
-                                  float* obar, const Geom& g, int64_t BH, hipStream_t stream)
+static hipError_t launch_coarse_t(const float* qbar, const float* kbar, const float* kbar_il,
+                                  const float* vbar, float* obar, const Geom& g, int64_t BH,
+                                  hipStream_t stream)
 {
     const int G = coarse_group_size(g.n_blocks, D);
     if (G == 0) return hipErrorInvalidValue;
@@ -203,17 +201,18 @@ static hipError_t launch_coarse_t(const float* qbar, const float* kbar, const fl
     }
     dim3 grid((unsigned)(BH * ((g.n_blocks + G - 1) / G)));
     hipLaunchKernelGGL((coarse_kernel<D>), grid, dim3(256), coarse_lds_bytes(G, g.n_blocks, D),
-                       stream, qbar, kbar, vbar, obar, g, G);
+                       stream, qbar, kbar, kbar_il, vbar, obar, g, G);
     return hipGetLastError();
 }
 
-hipError_t launch_coarse(const float* qbar, const float* kbar, const float* vbar, float* obar,
-                         const Geom& g, int D, int64_t BH, hipStream_t stream)
+hipError_t launch_coarse(const float* qbar, const float* kbar, const float* kbar_il,
+                         const float* vbar, float* obar, const Geom& g, int D, int64_t BH,
+                         hipStream_t stream)
 {
     switch (D) {
-    case 32: return launch_coarse_t<32>(qbar, kbar, vbar, obar, g, BH, stream);
-    case 64: return launch_coarse_t<64>(qbar, kbar, vbar, obar, g, BH, stream);
-    case 128: return launch_coarse_t<128>(qbar, kbar, vbar, obar, g, BH, stream);
+    case 32: return launch_coarse_t<32>(qbar, kbar, kbar_il, vbar, obar, g, BH, stream);
+    case 64: return launch_coarse_t<64>(qbar, kbar, kbar_il, vbar, obar, g, BH, stream);
+    case 128: return launch_coarse_t<128>(qbar, kbar, kbar_il, vbar, obar, g, BH, stream);
     }
     return hipErrorInvalidValue;
 }
