@@ -404,7 +404,10 @@ extern "C" int mosaic_bsa_bwd_three_branch(const mosaic_bsa_params* params, int3
                  sel_idx, dq, dk, dv, ws + w.attn, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     // coarse branch on the pooled tensors
-    if (bsa::launch_coarse_bwd(qbar, kbar, vbar, dobar, (float*)(ws + w.a_mat),
+    if (bsa::launch_coarse_bwd(qbar, kbar,
+                               bsa::select_interleaves_keys(c.g.n_blocks)
+                                   ? (const float*)(fw + f.keys) : nullptr,
+                               vbar, dobar, (float*)(ws + w.a_mat),
                                (float*)(ws + w.ds_mat), (float*)(ws + w.dqbar),
                                (float*)(ws + w.dkbar), (float*)(ws + w.dvbar), c.g, c.D, c.BH,
                                stream) != hipSuccess)

@@ -98,8 +98,8 @@ hipError_t launch_branch_grads(bool is_bf16, const float* obar, const void* o_fg
                                const float* gates, const void* dout, void* do_fg, void* do_l,
                                float* dgates, float* dobar, const Geom& g, int D, int64_t BH,
                                hipStream_t stream);
-hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* vbar,
-                             const float* dobar, float* a_mat, float* ds_mat, float* dqbar,
+hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* kbar_il,
+                             const float* vbar, const float* dobar, float* a_mat, float* ds_mat, float* dqbar,
                              float* dkbar, float* dvbar, const Geom& g, int D, int64_t BH,
                              hipStream_t stream);
 

@@ -401,20 +401,18 @@ __global__ __launch_bounds__(256) void gated_block_sum_kernel(const T* __restric
 }
 
 // Same workgroup shape as coarse_kernel (G <= 8 query blocks of one slice).
-// LDS: 2*G*D (pooled queries, dobar rows) + 4*G*D (partials) + 2*G*m
-// (weights, ds) floats.
+// LDS: 4*G*D (partials) + 2*G*m (weights, ds) floats.
 template <int D>
 __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
     const float* __restrict__ qbar, const float* __restrict__ kbar,
-    const float* __restrict__ vbar, const float* __restrict__ dobar, float* __restrict__ a_out,
-    float* __restrict__ ds_out, float* __restrict__ dqbar, Geom g, int G)
+    const float* __restrict__ kbar_il, const float* __restrict__ vbar,
+    const float* __restrict__ dobar, float* __restrict__ a_out, float* __restrict__ ds_out,
+    float* __restrict__ dqbar, Geom g, int G)
 {
     constexpr int CG = D / 4, JP = 256 / CG;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int m = g.n_blocks;
-    float* q_s = (float*)smem;                       // [G][D]
-    float* do_s = q_s + G * D;                       // [G][D]
-    float* red_s = do_s + G * D;                     // [4 wavefronts][G][D]
+    float* red_s = (float*)smem;                     // [4 wavefronts][G][D]
     float* sc_s = red_s + 4 * G * D;                 // [G][m]: scores -> weights a
     float* da_s = sc_s + G * m;                      // [G][m]: da -> ds
 
@@ -426,26 +424,26 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
     kbar += kv * m * D;
     vbar += kv * m * D;
     const int64_t row0 = bh_idx * m + i0;
+    if (kbar_il) kbar_il += kv * m * D;              // per slice [D/4][m][4]
 
-    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) {
-        q_s[e] = qbar[row0 * D + e];
-        do_s[e] = dobar[row0 * D + e];
-    }
-    __syncthreads();
-
-    // scores (base-2 domain) and da_ij = dobar_i . vbar_j
+    // scores (base-2 domain) and da_ij = dobar_i . vbar_j; the rows of qbar and
+    // dobar are wave-uniform (scalar loads, scalar operands of the fma)
     const float c2 = g.scale * kLog2e;
     for (int j = threadIdx.x; j < m; j += blockDim.x) {
         float kr[D];
+        const float4* ksrc = kbar_il ? (const float4*)kbar_il + j
+                                     : (const float4*)(kbar + (int64_t)j * D);
+        const int64_t kstep = kbar_il ? (int64_t)m : 1;
 #pragma unroll
         for (int d4 = 0; d4 < D / 4; ++d4) {
-            const float4 t = *(const float4*)(kbar + (int64_t)j * D + 4 * d4);
+            const float4 t = ksrc[d4 * kstep];
             kr[4 * d4 + 0] = t.x; kr[4 * d4 + 1] = t.y; kr[4 * d4 + 2] = t.z; kr[4 * d4 + 3] = t.w;
         }
         for (int r = 0; r < rows; ++r) {
+            const float* __restrict__ qrow = qbar + (row0 + r) * D;
             float acc = 0.0f;
 #pragma unroll
-            for (int d = 0; d < D; ++d) acc = fmaf(q_s[r * D + d], kr[d], acc);
+            for (int d = 0; d < D; ++d) acc = fmaf(qrow[d], kr[d], acc);
             sc_s[r * m + j] = acc * c2;
         }
 #pragma unroll
@@ -454,9 +452,10 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
             kr[4 * d4 + 0] = t.x; kr[4 * d4 + 1] = t.y; kr[4 * d4 + 2] = t.z; kr[4 * d4 + 3] = t.w;
         }
         for (int r = 0; r < rows; ++r) {
+            const float* __restrict__ dorow = dobar + (row0 + r) * D;
             float acc = 0.0f;
 #pragma unroll
-            for (int d = 0; d < D; ++d) acc = fmaf(do_s[r * D + d], kr[d], acc);
+            for (int d = 0; d < D; ++d) acc = fmaf(dorow[d], kr[d], acc);
             da_s[r * m + j] = acc;
         }
     }
@@ -539,7 +538,7 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
 
 static size_t coarse_bwd_lds_bytes(int G, int m, int D)
 {
-    return ((size_t)2 * G * D + (size_t)4 * G * D + (size_t)2 * G * m) * 4;
+    return ((size_t)4 * G * D + (size_t)2 * G * m) * 4;
 }
 
 int coarse_bwd_group_size(int m, int D)
@@ -632,8 +631,8 @@ hipError_t launch_branch_grads(bool is_bf16, const float* obar, const void* o_fg
 }
 
 template <int D>
-static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, const float* vbar,
-                                      const float* dobar, float* a_mat, float* ds_mat,
+static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, const float* kbar_il,
+                                      const float* vbar, const float* dobar, float* a_mat, float* ds_mat,
                                       float* dqbar, float* dkbar, float* dvbar, const Geom& g,
                                       int64_t BH, hipStream_t stream)
 {
@@ -651,8 +650,8 @@ static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, cons
     }
     const int m = g.n_blocks;
     hipLaunchKernelGGL((coarse_bwd_rows_kernel<D>), dim3((unsigned)(BH * ((m + G - 1) / G))),
-                       dim3(256), coarse_bwd_lds_bytes(G, m, D), stream, qbar, kbar, vbar, dobar,
-                       a_mat, ds_mat, dqbar, g, G);
+                       dim3(256), coarse_bwd_lds_bytes(G, m, D), stream, qbar, kbar, kbar_il, vbar,
+                       dobar, a_mat, ds_mat, dqbar, g, G);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t BKV = BH / g.kv_group;
@@ -662,15 +661,15 @@ static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, cons
     return hipGetLastError();
 }
 
-hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* vbar,
-                             const float* dobar, float* a_mat, float* ds_mat, float* dqbar,
+hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* kbar_il,
+                             const float* vbar, const float* dobar, float* a_mat, float* ds_mat, float* dqbar,
                              float* dkbar, float* dvbar, const Geom& g, int D, int64_t BH,
                              hipStream_t stream)
 {
     switch (D) {
-    case 32: return launch_coarse_bwd_t<32>(qbar, kbar, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
-    case 64: return launch_coarse_bwd_t<64>(qbar, kbar, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
-    case 128: return launch_coarse_bwd_t<128>(qbar, kbar, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
+    case 32: return launch_coarse_bwd_t<32>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
+    case 64: return launch_coarse_bwd_t<64>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
+    case 128: return launch_coarse_bwd_t<128>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
     }
     return hipErrorInvalidValue;
 }
