@@ -192,6 +192,20 @@ def test_selection_with_many_blocks(G, oracle, H, W, bh, bw, D, n, dtype):
         assert idx[0, 1, i].tolist() == [j for j in range(cfg.n_blocks) if j != i][:n]
 
 
+def test_selection_with_more_blocks_than_registers_hold(G, oracle):
+    """m > 4096: the fused kernel again, with fewer query blocks per workgroup
+    and a top-n that rescans LDS after every pick."""
+    cfg = shape_ns(1, 2, 96, 96, 1, 2, 32, 3, "fp32")          # m = 4608
+    assert cfg.n_blocks == 4608
+    s = oracle.shape_of(cfg)
+    q, k, _ = rand_qkv(cfg, 950)
+    assert np.array_equal(G.gpu_select(cfg, q, k), oracle.select(s, q, k))
+    rng = np.random.default_rng(951)
+    qq = (rng.integers(-8, 9, size=q.shape) / 4).astype(np.float32)
+    kq = (rng.integers(-2, 3, size=q.shape) / 4).astype(np.float32)   # many exact ties
+    assert np.array_equal(G.gpu_select(cfg, qq, kq), oracle.select(s, qq, kq))
+
+
 @pytest.mark.parametrize("dtype,B,heads,kv_heads,H,W,bh,bw,D,n", [
     ("fp32", 1, 1, 1, 32, 64, 8, 8, 32, 5),       # one slice: a single part
     ("fp32", 1, 3, 3, 32, 64, 8, 8, 32, 5),       # three slices: three parts
