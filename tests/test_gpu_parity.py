@@ -559,6 +559,7 @@ def test_three_branch_paper_stage2_layer_reduced_batch(G, oracle):
     ("bf16", 1, 4, 1, 32, 64, 8, 8, 64, 1, 1, 1),     # n = 1, local block = the tile itself
     ("bf16", 1, 8, 2, 16, 256, 1, 128, 64, 5, 2, 2),  # block-contiguous 128-token blocks, grouped
     ("bf16", 2, 2, 0, 32, 64, 8, 16, 128, 3, 2, 2),   # head dim 128 matrix-core kernels
+    ("fp32", 1, 2, 0, 80, 120, 4, 4, 32, 6, 2, 2),    # m = 600: no interleaved copy of the pooled keys
 ])
 def test_three_branch_backward(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n, lh, lw):
     """Gradients of the three-branch form with the selection held fixed,
