@@ -226,9 +226,15 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
         return (uint32_t)((br * g.block_h * g.grid_w + bc * g.block_w) * (D * 2));
     };
     const int pairs = (n + 1) * subs;
+    // the listed blocks sit in the lanes of one register (up to 64 of them), so
+    // that finding the next tile costs no memory access inside the loop
+    const int sel_mine = (n <= 64 && lane < n) ? sel_row[lane] : 0;
     auto origin_of_pair = [&](int c) -> uint32_t {   // attended block c / subs, sub-tile c % subs
         const int cb = c / subs, ct = c - cb * subs;
-        return origin_of(cb == 0 ? first : sel_row[cb - 1]) + (uint32_t)(sub_tile_first(g, ct) * (D * 2));
+        const int beta = cb == 0 ? first
+                                 : (n <= 64 ? __builtin_amdgcn_readlane(sel_mine, cb - 1)
+                                            : sel_row[cb - 1]);
+        return origin_of(beta) + (uint32_t)(sub_tile_first(g, ct) * (D * 2));
     };
 
     io.gather(k_rsrc, origin_of_pair(0), k_lds[0]);
@@ -259,6 +265,141 @@ __device__ __forceinline__ void dq_body(const uint16_t* __restrict__ q,
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[dt] = zero_tile();
 
+    if constexpr (D == 64) {
+        // Software pipeline over the 32-key halves of the tiles: the
+        // exponentials and products that turn S^T, dP^T of one half into dS^T
+        // are issued behind the matrix instructions of the next half, two
+        // elements per instruction slot, in an order that is written out and
+        // pinned (the scheduler would otherwise group them after the matrix
+        // instructions, and the two wavefronts of a SIMD do not overlap such
+        // phases for each other).  Per tile:
+        //   G1  S^T, dP^T of half 0 (8 slots)      | dS^T of the previous half 1
+        //   G2  dQ^T += K^T dS^T of the previous half 1 (4 slots),
+        //       S^T, dP^T of half 1 (8 slots)      | dS^T of half 0
+        //   G3  dQ^T += K^T dS^T of half 0 (4 slots)
+        // Carried between tiles: S^T, dP^T of half 1 and its transposed K
+        // fragments.  The sums run in the same order as in the plain loop below.
+        f32x16 s1, dp1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s1[r] = -1.0e30f; dp1[r] = 0.0f; }   // weights 0
+        bf16x8 ktf[2][2];                                  // [h][dt]
+        {
+            const bf16x8 z = __builtin_bit_cast(bf16x8, make_uint4(0u, 0u, 0u, 0u));
+            ktf[0][0] = z; ktf[0][1] = z; ktf[1][0] = z; ktf[1][1] = z;
+        }
+        // dS^T of elements 2k, 2k+1 of a half, packed
+        auto ds_pair = [&](const f32x16& sv, const f32x16& dpv, int k) -> uint32_t {
+            const float f0 = fmaf(sv[2 * k], c2, neg_l2), f1 = fmaf(sv[2 * k + 1], c2, neg_l2);
+            const float d0 = dpv[2 * k] - dl, d1 = dpv[2 * k + 1] - dl;
+            const float e0 = __builtin_amdgcn_exp2f(f0), e1 = __builtin_amdgcn_exp2f(f1);
+            return pack_bf16(e0 * d0, e1 * d1);
+        };
+        // an empty statement that "uses" a slot's result keeps its producers in
+        // the slot; no instruction is emitted for it
+        auto pin = [](uint32_t& w) {
+            asm volatile("" : "+v"(w));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        for (int c = 0; c < pairs; ++c) {
+            // tile c has landed (own loads, then everyone's), every LDS read of
+            // the tile before has returned and everyone is done with the other
+            // buffer: refill it with tile c + 1
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (c + 1 < pairs) {
+                const uint32_t o = origin_of_pair(c + 1);
+                io.gather(k_rsrc, o, k_lds[(c + 1) & 1]);
+                io.gather(v_rsrc, o, v_lds[(c + 1) & 1]);
+            }
+            const unsigned char* kt_lds = k_lds[c & 1];
+            const unsigned char* vt_lds = v_lds[c & 1];
+            bf16x8 kf[KS], vf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                kf[ks] = row_frag<D>(kt_lds, 0, ks, l32, half);
+                vf[ks] = row_frag<D>(vt_lds, 0, ks, l32, half);
+            }
+            f32x16 s0 = zero_tile(), dp0 = zero_tile();
+            uint32_t w[8];
+            __builtin_amdgcn_sched_barrier(0);
+            // ---- G1
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (k < 4)
+                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k], qf[k], s0, 0, 0, 0);
+                else
+                    dp0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k - 4], dof[k - 4], dp0, 0, 0,
+                                                                  0);
+                if (k == 3) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) kf[ks] = row_frag<D>(kt_lds, 32, ks, l32, half);
+                }
+                if (k == 7) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) vf[ks] = row_frag<D>(vt_lds, 32, ks, l32, half);
+                }
+                w[k] = ds_pair(s1, dp1, k);
+                pin(w[k]);
+            }
+            bf16x8 dsb[2];
+            dsb[0] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            dsb[1] = __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7]));
+            // ---- G2
+            s1 = zero_tile();
+            dp1 = zero_tile();
+#pragma unroll
+            for (int k = 0; k < 12; ++k) {
+                if (k < 4)
+                    acc[k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[k >> 1][k & 1],
+                                                                         dsb[k >> 1], acc[k & 1],
+                                                                         0, 0, 0);
+                else if (k < 8)
+                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k - 4], qf[k - 4], s1, 0, 0, 0);
+                else
+                    dp1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[k - 8], dof[k - 8], dp1, 0, 0,
+                                                                  0);
+                if (k == 3) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt)
+                            ktf[h][dt] = trans_frag<D>(kt_lds, 16 * h, dt, lane);
+                }
+                if (k >= 2 && k < 10) {
+                    w[k - 2] = ds_pair(s0, dp0, k - 2);
+                    pin(w[k - 2]);
+                } else {
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            dsb[0] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            dsb[1] = __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7]));
+            // ---- G3
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                acc[k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[k >> 1][k & 1], dsb[k >> 1],
+                                                                     acc[k & 1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+                    ktf[h][dt] = trans_frag<D>(kt_lds, 32 + 16 * h, dt, lane);
+        }
+        // the last half 1
+        {
+            uint32_t w[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) w[k] = ds_pair(s1, dp1, k);
+            bf16x8 dsb[2];
+            dsb[0] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            dsb[1] = __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7]));
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                acc[k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[k >> 1][k & 1], dsb[k >> 1],
+                                                                     acc[k & 1], 0, 0, 0);
+        }
+    } else
     for (int c = 0; c < pairs; ++c) {
         // tile c has landed (own loads, then everyone's) and everyone is done
         // with the other buffer: refill it with tile c + 1
