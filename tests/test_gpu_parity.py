@@ -7,6 +7,8 @@ mode; lse within 3e-3 (bf16) / 1e-5 relative (fp32).  The bf16 lse bound follows
 from the kernel's arithmetic: the normaliser is the sum of the bf16-rounded
 weights that enter the PV product, so it carries a relative error of at most
 2^-9 (one key dominating), i.e. ln(1 + 2^-9) = 1.95e-3 in lse, plus fp32 noise."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -29,7 +31,7 @@ def check_out(cfg, out_gpu, lse_gpu, out_ref, lse_ref):
     if cfg.dtype == "bf16":
         err = np.abs(out_gpu - out_ref).max()
         assert err <= 2e-2, f"bf16 max-abs error {err}"
-        assert np.abs(lse_gpu - lse_ref).max() <= 3e-3
+        assert np.abs(lse_gpu - lse_ref).max() <= 1e-3
     else:
         rel = np.abs(out_gpu - out_ref).max() / max(np.abs(out_ref).max(), 1e-30)
         assert rel <= 1e-5, f"fp32 relative error {rel}"
@@ -329,7 +331,7 @@ def full_size_check(G, oracle, p, pairs):
         l = lse_t[int(g)][rows].cpu().numpy()
         assert np.isfinite(o).all()
         assert np.abs(o - out_ref[w]).max() <= 2e-2, (g, i)
-        assert np.abs(l - lse_ref[w]).max() <= 3e-3, (g, i)
+        assert np.abs(l - lse_ref[w]).max() <= 1e-3, (g, i)
     # every output row was written (the buffers were pre-filled with NaN)
     assert bool(torch.isfinite(out_d.float()).all()) and bool(torch.isfinite(lse_d).all())
 
@@ -349,7 +351,7 @@ def test_config4_full_size_sampled(G, oracle):
     cfg = p.cfg
     rng = np.random.default_rng(44)
     pairs = [[int(g), int(i)] for g in range(cfg.batch * cfg.heads)
-             for i in rng.choice(cfg.n_blocks, size=3, replace=False)]
+             for i in rng.choice(cfg.n_blocks, size=41, replace=False)]   # 1 % of the query blocks
     full_size_check(G, oracle, p, np.array(pairs))
 
 
@@ -358,7 +360,7 @@ def test_config5_full_size_forward_sampled(G, oracle):
     cfg = p.cfg
     rng = np.random.default_rng(55)
     pairs = [[int(g), int(i)] for g in rng.choice(cfg.batch * cfg.heads, size=8, replace=False)
-             for i in rng.choice(cfg.n_blocks, size=4, replace=False)]
+             for i in rng.choice(cfg.n_blocks, size=20, replace=False)]
     full_size_check(G, oracle, p, np.array(pairs))
 
 
@@ -437,6 +439,82 @@ def test_backward_matrix_core_shapes(G, oracle, H, W, bh, bw, D, n):
     ref = oracle.bwd(s, q, k, v, dout, idx)
     got = G.gpu_bwd(cfg, q, k, v, dout, idx)
     check_grads(cfg, got, ref)
+
+
+@pytest.mark.parametrize("H,W,bh,bw,D,n,sel_seed", [
+    (96, 128, 8, 8, 64, 5, 43),      # 64-token blocks: rounds of 128 query blocks, m = 192
+    (136, 256, 8, 16, 128, 3, 44),   # 128-token blocks, head dim 128: rounds of 256, m = 272
+    (34, 1024, 1, 128, 64, 4, 45),   # block-contiguous 128-token blocks, head dim 64, m = 272
+    (384, 384, 16, 16, 64, 1, 46),   # 256-token blocks: rounds of 512, m = 576
+    (72, 80, 8, 8, 64, 70, 47),      # n > 64: the attended blocks do not fit one wavefront
+    (40, 128, 8, 8, 64, 0, 0),       # n = 0 with several rounds: only the own block is connected
+])
+def test_backward_with_more_query_blocks_than_one_scan_round(G, oracle, H, W, bh, bw, D, n,
+                                                             sel_seed):
+    """The dK/dV kernels collect the query blocks connected to a key block in
+    rounds of 64 x (wavefronts per workgroup) candidates; these shapes need two
+    or more rounds per key block (the benchmark configurations need four to
+    eight), and one of them has more attended blocks than a wavefront has
+    lanes.  Arbitrary valid selections in random order."""
+    cfg = shape_ns(1, 2, H, W, bh, bw, D, n, "bf16")
+    q, k, v = (round_to_bf16(x) for x in rand_qkv(cfg, 950 + bh + D + n))
+    dout = round_to_bf16(rand_qkv(cfg, 951 + bh + D + n)[0])
+    s = oracle.shape_of(cfg)
+    idx = random_selection(cfg, sel_seed) if n else oracle.select(s, q, k)
+    ref = oracle.bwd(s, q, k, v, dout, idx)
+    got = G.gpu_bwd(cfg, q, k, v, dout, idx)
+    check_grads(cfg, got, ref)
+
+
+def slices_against_oracle_bwd(G, oracle, p, slices, idx_d=None):
+    """Forward + backward of the whole problem on the GPU (the launch
+    configuration the benchmark times); the gradients of the given (batch, head)
+    slices against the oracle, which treats them as the heads of one entry."""
+    import paper_2604_16429_amd as M
+    from paper_2604_16429_amd import binding
+    cfg = p.cfg
+    prm = G.params_of(cfg)
+    q_d, k_d, v_d, do_d = (G.to_dev(x, cfg) for x in (p.q, p.k, p.v, p.dout))
+    if idx_d is None:
+        idx_d = G.select_dev(cfg, q_d, k_d)
+    out, lse = G.fwd_dev(cfg, q_d, k_d, v_d, idx_d)
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q_d, k_d, v_d))
+    ws = torch.empty(M.mosaic_bsa_workspace_bytes(prm, binding.OP_BWD), dtype=torch.uint8,
+                     device="cuda")
+    M.mosaic_bsa_bwd(prm, q_d, k_d, v_d, out, lse, do_d, idx_d, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv):
+        assert bool(torch.isfinite(t.float()).all())        # every row was written
+    idx = idx_d.cpu().numpy()
+    pick = lambda x: np.stack([x[e, a] for e, a in slices])[None]
+    sub = dataclasses.replace(cfg, batch=1, heads=len(slices))
+    ref = oracle.bwd(oracle.shape_of(sub), pick(p.q), pick(p.k), pick(p.v), pick(p.dout),
+                     pick(idx))
+    got = tuple(pick(t.float().cpu().numpy()) for t in (dq, dk, dv))
+    check_grads(cfg, got, ref)
+    return idx_d, (dq, dk, dv)
+
+
+def test_backward_gradient_configuration_full_grid(G, oracle):
+    """The gradient configuration at its full size (120 x 240 grid, batch 4, 16
+    heads, head dim 128, tiles of 8 x 16, 12 selected blocks, dO white): the
+    GPU's own selection, forward and backward of the whole problem; dQ, dK, dV
+    of two whole (batch, head) slices against the oracle's closed forms."""
+    p = make_problem(5)
+    slices_against_oracle_bwd(G, oracle, p, [(1, 3), (3, 14)])
+
+
+def test_backward_ensemble_shape_full_grid(G, oracle):
+    """The 1.5 degree ensemble shape (m = 450 blocks of 64 tokens, head dim 64,
+    16 selected blocks: four scan rounds per key block) at a reduced batch, dO
+    white; two whole slices against the oracle; reruns are bitwise identical."""
+    p = make_problem(3, batch=2, heads=4)
+    rng = np.random.default_rng(35)
+    p.dout = round_to_bf16(rng.standard_normal(p.q.shape).astype(np.float32))
+    idx_d, first = slices_against_oracle_bwd(G, oracle, p, [(0, 1), (1, 2)])
+    _, second = slices_against_oracle_bwd(G, oracle, p, [(1, 3)], idx_d)
+    for a, b in zip(first, second):
+        assert torch.equal(a, b)
 
 
 def test_backward_gradient_configuration_fields(G, oracle):
@@ -560,6 +638,8 @@ def test_three_branch_paper_stage2_layer_reduced_batch(G, oracle):
     ("bf16", 1, 8, 2, 16, 256, 1, 128, 64, 5, 2, 2),  # block-contiguous 128-token blocks, grouped
     ("bf16", 2, 2, 0, 32, 64, 8, 16, 128, 3, 2, 2),   # head dim 128 matrix-core kernels
     ("fp32", 1, 2, 0, 80, 120, 4, 4, 32, 6, 2, 2),    # m = 600: no interleaved copy of the pooled keys
+    ("bf16", 1, 2, 0, 96, 128, 8, 8, 64, 4, 2, 2),    # m = 192: the lists span two scan rounds of dK/dV
+    ("bf16", 1, 4, 2, 34, 1024, 1, 128, 64, 3, 2, 4), # m = 272, 128-token blocks, grouped heads
 ])
 def test_three_branch_backward(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n, lh, lw):
     """Gradients of the three-branch form with the selection held fixed,
