@@ -39,7 +39,7 @@
 // (4 MFMAs) -- are software-pipelined across tiles, also across pair
 // boundaries: step s issues, alternating, the 4 MFMAs of S(s+1) and the 4 MFMAs
 // of the O update with P(s-1), and behind each of these 8 MFMAs one eighth of
-// the weights of tile s (2 fma, 2 exp2, 1 convert, 1 dot for the row sum).
+// the weights of tile s (2 fma, 2 exp2, 1 rounding pack, 2 adds for the row sum).
 // Only two S tiles and two P tiles are live, so the wavefront fits 256
 // registers and two wavefronts share a SIMD to cover each other's waits.
 //
@@ -103,10 +103,11 @@ struct Refill {
 // tile J = (key half J/2, query half J%2).  Issues, alternating, the 4 MFMAs of
 // the S tile J+1 and the 4 MFMAs that add tile J-1 to O, and behind each the
 // vector work of one eighth of the weights of tile J, skewed by one slot
-// (fma for slot k+1, exp2 for slot k, convert + row sum for slot k-1) so that
-// no instruction waits for the one before it.  With REFILL, slot r also issues
-// slab r of a K/V refill.  S tiles and P tiles are indexed by query half: the
-// tile being weighted and its neighbours in the pipeline always differ in it.
+// (fma for slot k+1, exp2 for slot k, rounding pack + row sum for slot k-1) so
+// that no instruction waits for the one before it.  With REFILL, slot r also
+// issues slab r of a K/V refill.  S tiles and P tiles are indexed by query
+// half: the tile being weighted and its neighbours in the pipeline always
+// differ in it.  Returns this lane's sum of the tile's fp32 weights.
 template <int J, bool REFILL, int NW, class Mid>
 __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2],
                                                f32x16 (&oacc)[2][2], const bf16x8 (&qf)[2][4],
@@ -122,8 +123,8 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
     const f32x16 zero16 = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
                            0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     uint32_t w[8];
-    float rs0 = 0.0f, rs1 = 0.0f;
-    float f[9][2], e[8][2];
+    float rs0, rs1;
+    float f[8][2], e[8][2];
     f[0][0] = fmaf(s[nt][0], c2, neg_m);
     f[0][1] = fmaf(s[nt][1], c2, neg_m);
     asm volatile("" : "+v"(f[0][0]), "+v"(f[0][1]));
@@ -156,31 +157,41 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
                     16, voff[k], rf.origin_b, 0, 0);
         }
         // exp2 of this slot's pair, fma of the next slot's, pack and row sums
-        // of the previous slot's: nothing waits for the instruction before it
+        // of the previous slot's: nothing waits for the instruction before it.
+        // The empty asm statements "use" the slot's results: they keep their
+        // producers in this slot (they would otherwise sink to the first real
+        // use, after the last MFMA); no instruction is emitted for them.
         e[k][0] = __builtin_amdgcn_exp2f(f[k][0]);
         e[k][1] = __builtin_amdgcn_exp2f(f[k][1]);
         if (k + 1 < 8) {
             f[k + 1][0] = fmaf(s[nt][2 * k + 2], c2, neg_m);
             f[k + 1][1] = fmaf(s[nt][2 * k + 3], c2, neg_m);
-        } else {
-            f[k + 1][0] = 0.0f; f[k + 1][1] = 0.0f;
         }
-        if (k >= 1) {
-            w[k - 1] = pack_bf16_trunc(e[k - 1][0], e[k - 1][1]);
+        if (k >= 1) w[k - 1] = pack_bf16(e[k - 1][0], e[k - 1][1]);
+        if (k == 2) {
+            rs0 = e[0][0] + e[1][0];
+            rs1 = e[0][1] + e[1][1];
+        } else if (k > 2) {
             rs0 += e[k - 1][0];
             rs1 += e[k - 1][1];
-        } else {
-            w[7] = 0;
         }
-        // an empty statement that "uses" the slot's results: it keeps their
-        // producers in this slot (they would otherwise sink to the first real
-        // use, after the last MFMA); no instruction is emitted for it
-        asm volatile(""
-                     : "+v"(e[k][0]), "+v"(e[k][1]), "+v"(f[k + 1][0]), "+v"(f[k + 1][1]),
-                       "+v"(w[k >= 1 ? k - 1 : 7]), "+v"(rs0), "+v"(rs1));
+        if (k == 0)
+            asm volatile("" : "+v"(e[0][0]), "+v"(e[0][1]), "+v"(f[1][0]), "+v"(f[1][1]));
+        else if (k == 1)
+            asm volatile(""
+                         : "+v"(e[1][0]), "+v"(e[1][1]), "+v"(f[2][0]), "+v"(f[2][1]),
+                           "+v"(w[0]));
+        else if (k < 7)
+            asm volatile(""
+                         : "+v"(e[k][0]), "+v"(e[k][1]), "+v"(f[k < 7 ? k + 1 : 7][0]),
+                           "+v"(f[k < 7 ? k + 1 : 7][1]), "+v"(w[k >= 1 ? k - 1 : 0]), "+v"(rs0),
+                           "+v"(rs1));
+        else
+            asm volatile(""
+                         : "+v"(e[7][0]), "+v"(e[7][1]), "+v"(w[6]), "+v"(rs0), "+v"(rs1));
         __builtin_amdgcn_sched_barrier(0);
     }
-    w[7] = pack_bf16_trunc(e[7][0], e[7][1]);
+    w[7] = pack_bf16(e[7][0], e[7][1]);
     rs0 += e[7][0];
     rs1 += e[7][1];
     p[nt][0] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
@@ -508,7 +519,7 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const float l_tot = l_run[nt] + swap32(l_run[nt]);
-        const float inv_l = (1.0f / (1.0f - kTruncLoss)) / l_tot;
+        const float inv_l = 1.0f / l_tot;
         uint16_t* orow = out + q_tok[nt] * D;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)

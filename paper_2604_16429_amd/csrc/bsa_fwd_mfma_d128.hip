@@ -16,7 +16,7 @@
 // registers are the B operand of the second product), K fragments from 16-byte
 // LDS reads, V^T fragments from the transposing LDS read, K/V gathered with
 // direct-to-LDS buffer loads whose lane-to-chunk mapping applies the LDS
-// swizzle on the global side, weights packed to bf16 by truncation with the
+// swizzle on the global side, weights rounded to bf16 (nearest even) with the
 // normaliser summed in fp32, and no row maximum per tile (slow path only when
 // a row sum leaves the safe range).
 //
@@ -359,7 +359,7 @@ __device__ __forceinline__ void fwd_mfma_q32_body(
                     f[ch + 1][0] = 0.0f; f[ch + 1][1] = 0.0f;
                 }
                 if (ch >= 1) {
-                    w[ch - 1] = pack_bf16_trunc(e[ch - 1][0], e[ch - 1][1]);
+                    w[ch - 1] = pack_bf16(e[ch - 1][0], e[ch - 1][1]);
                     rs0 += e[ch - 1][0];
                     rs1 += e[ch - 1][1];
                 } else {
@@ -376,7 +376,7 @@ __device__ __forceinline__ void fwd_mfma_q32_body(
         }
         // the O MFMAs have been issued: the V fragment registers are free
         read_v_half(v_next_lds);
-        w[7] = pack_bf16_trunc(e[7][0], e[7][1]);
+        w[7] = pack_bf16(e[7][0], e[7][1]);
         rs0 += e[7][0];
         rs1 += e[7][1];
         p[J][0] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
@@ -454,7 +454,7 @@ __device__ __forceinline__ void fwd_mfma_q32_body(
     // ---- normalise, store O rows (4 consecutive channels per store)
     {
         const float l_tot = l_run + swap32(l_run);
-        const float inv_l = (1.0f / (1.0f - kTruncLoss)) / l_tot;
+        const float inv_l = 1.0f / l_tot;
         uint16_t* orow = out + q_tok * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)

@@ -26,18 +26,8 @@ __device__ __forceinline__ float swap32(float x)
     return __uint_as_float(threadIdx.x & 32 ? r[0] : r[1]);
 }
 
-// Two fp32 weights -> bf16 pair by truncation (one byte-permute instead of the
-// half-rate rounding convert).  Truncation loses, on average over mantissas,
-// the fraction kTruncLoss of a weight; the normaliser is summed from the fp32
-// weights, so the epilogue scales the output by 1 / (1 - kTruncLoss).
-// (mean of half an ulp, 2^-8, over a log-uniform mantissa m: 2^-8 E[1/m] =
-// 2^-8 / (2 ln 2).)
-constexpr float kTruncLoss = 0.0028179f;
-__device__ __forceinline__ uint32_t pack_bf16_trunc(float lo, float hi)
-{
-    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
-}
-
+// Two fp32 values -> bf16 pair, round to nearest even (v_cvt_pk_bf16_f32; it
+// issues at the rate of any other three-operand vector instruction).
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 {
     const f32x2 v = {a, b};
@@ -45,10 +35,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
-// P^T = exp2(S^T c2 - m_ref) for one 32-key x 32-query tile, packed to bf16 B
-// operands; returns this lane's sum of the rounded weights (two per
-// instruction).  Only builtins touch the MFMA results (never inline asm): the
-// compiler must see these reads to place the wait states the hardware requires.
+// P^T = exp2(S^T c2 - m_ref) for one 32-key x 32-query tile, rounded to bf16 B
+// operands; returns this lane's sum of the fp32 weights.  Only builtins touch
+// the MFMA results (never inline asm): the compiler must see these reads to
+// place the wait states the hardware requires.
 __device__ __forceinline__ float tile_weights(const f32x16& s, float c2, float neg_m,
                                               bf16x8 (&p)[2])
 {
@@ -60,7 +50,7 @@ __device__ __forceinline__ float tile_weights(const f32x16& s, float c2, float n
         for (int e = 0; e < 4; ++e) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(s[8 * h + 2 * e], c2, neg_m));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(s[8 * h + 2 * e + 1], c2, neg_m));
-            w[e] = pack_bf16_trunc(p0, p1);
+            w[e] = pack_bf16(p0, p1);
             rs += p0 + p1;
         }
         p[h] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));

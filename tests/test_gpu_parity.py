@@ -3,10 +3,9 @@ oracle on the same seeded inputs.
 
 Bars: selected indices bit-exact (element for element, in the emitted order);
 outputs within 1e-5 of max|O| in fp32 mode and within 2e-2 max-abs in bf16
-mode; lse within 3e-3 (bf16) / 1e-5 relative (fp32).  The bf16 lse bound follows
-from the kernel's arithmetic: the normaliser is the sum of the bf16-rounded
-weights that enter the PV product, so it carries a relative error of at most
-2^-9 (one key dominating), i.e. ln(1 + 2^-9) = 1.95e-3 in lse, plus fp32 noise."""
+mode; lse within 1e-3 (bf16) / 1e-5 relative (fp32).  The matrix-core kernels
+round the attention weights to bf16 (nearest even) for the PV product and sum
+the normaliser from the fp32 weights, so lse carries fp32 noise only."""
 import dataclasses
 
 import numpy as np
@@ -750,7 +749,8 @@ def test_large_logits_with_rising_maxima(G, oracle, bh, bw, D):
     index: the kernels visit blocks in ascending order, so the running
     reference of the softmax has to be replaced again and again (the slow
     path of the matrix-core kernels); forward and backward must stay within
-    the usual bounds and free of NaN / inf."""
+    the usual bounds (outputs of magnitude up to about 5 here: the plain 2e-2
+    bound is 1.25 bf16 half-ulps of the largest entries) and free of NaN / inf."""
     H, W = 4 * bh, 6 * bw
     cfg = shape_ns(1, 2, H, W, bh, bw, D, 9, "bf16")
     q, k, v = rand_qkv(cfg, 1234 + D)
@@ -767,12 +767,11 @@ def test_large_logits_with_rising_maxima(G, oracle, bh, bw, D):
     assert np.abs(lse_ref).max() > 40.0                 # the logits really are large
     out, lse = G.gpu_fwd(cfg, q, k, v, idx)
     assert np.isfinite(out).all() and np.isfinite(lse).all()
-    # Rows dominated by one key return (nearly) that key's value row, entries of
-    # magnitude up to 4 here: the bound scales with the output's magnitude (bf16
-    # output rounding alone is 2^-9 relative; the weights are packed to bf16 by
-    # truncation, which for a single dominant weight is not averaged out)
-    assert np.abs(out - out_ref).max() <= 2e-2 * max(1.0, np.abs(out_ref).max() / 2.0)
-    assert np.abs(lse - lse_ref).max() <= 3e-3 * max(1.0, np.abs(lse_ref).max() / 8.0)
+    err = np.abs(out - out_ref).max()
+    print(f"stress: max|O| {np.abs(out_ref).max():.3f} max-abs error {err:.4f} "
+          f"lse error {np.abs(lse - lse_ref).max():.2e}")
+    assert err <= 2e-2
+    assert np.abs(lse - lse_ref).max() <= 1e-3
     got = G.gpu_bwd(cfg, q, k, v, dout, idx)
     ref = oracle.bwd(s, q, k, v, dout, idx)
     for g_, r_ in zip(got, ref):
