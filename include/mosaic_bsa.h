@@ -80,7 +80,7 @@ enum { MOSAIC_BSA_OP_SELECT = 0, MOSAIC_BSA_OP_FWD = 1, MOSAIC_BSA_OP_BWD = 2 };
 /* Statement of the problem, in the paper's terms. */
 typedef struct {
     int32_t batch;          /* B */
-    int32_t heads;          /* query heads == key/value heads */
+    int32_t heads;          /* query heads (key/value heads: kv_heads below) */
     int32_t grid_h, grid_w; /* H, W: lat-lon grid, N = H*W tokens */
     int32_t block_h, block_w; /* tile shape; must divide H and W; b <= 1024 */
     int32_t head_dim;       /* d_k, one of 32, 64, 128 */
@@ -127,7 +127,8 @@ int mosaic_bsa_select(const mosaic_bsa_params *params, const void *q, const void
 /*
  * Block-sparse attention forward (fine-grained attention equation over the
  * union of the query block itself and its selected blocks, one softmax).
- *   q, k, v   in   device, [B, heads, N, D]
+ *   q         in   device, [B, heads, N, D]
+ *   k, v      in   device, [B, kv_heads, N, D]
  *   sel_idx   in   device, int32 [B, heads, m, n]; every entry in [0, m),
  *                  no duplicates within a row, never the row's own block;
  *                  any order.  Entries are trusted: an out-of-range index is
@@ -144,10 +145,13 @@ int mosaic_bsa_fwd(const mosaic_bsa_params *params, const void *q, const void *k
 /*
  * Backward of mosaic_bsa_fwd with sel_idx held fixed (no gradient flows
  * through the top-n choice).
- *   q, k, v, out, dout  in   device, [B, heads, N, D]
+ *   q, out, dout        in   device, [B, heads, N, D]
+ *   k, v                in   device, [B, kv_heads, N, D]
  *   lse                 in   device, fp32 [B, heads, N] as written by fwd
  *   sel_idx             in   device, same contract as in mosaic_bsa_fwd
- *   dq, dk, dv          out  device, [B, heads, N, D], element type of q
+ *   dq                  out  device, [B, heads, N, D], element type of q
+ *   dk, dv              out  device, [B, kv_heads, N, D] (summed over the query
+ *                            heads that share a key/value head)
  *   workspace                device scratch of
  *                            mosaic_bsa_workspace_bytes(.., OP_BWD) bytes; on
  *                            return its first half holds delta_l = dout_l . out_l,

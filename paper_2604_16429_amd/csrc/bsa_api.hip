@@ -209,7 +209,9 @@ extern "C" size_t mosaic_bsa_three_branch_workspace_bytes(const mosaic_bsa_param
 {
     Checked c;
     if (check_params(params, &c, true) || check_local(params, local_h, local_w)) return 0;
-    if (bsa::select_group_size(c.g.n_blocks, c.D) == 0) return 0;
+    if (bsa::select_group_size(c.g.n_blocks, c.D) == 0 ||
+        bsa::coarse_group_size(c.g.n_blocks, c.D) == 0)
+        return 0;
     return three_branch_layout(c, local_h * local_w).total;
 }
 
@@ -226,7 +228,9 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) ||
         misaligned(workspace))
         return MOSAIC_BSA_ERR_ALIGN;
-    if (bsa::select_group_size(c.g.n_blocks, c.D) == 0) return MOSAIC_BSA_ERR_SHAPE;
+    if (bsa::select_group_size(c.g.n_blocks, c.D) == 0 ||
+        bsa::coarse_group_size(c.g.n_blocks, c.D) == 0)
+        return MOSAIC_BSA_ERR_SHAPE;
     const int local_tiles = local_h * local_w;
     const ThreeBranchLayout w = three_branch_layout(c, local_tiles);
     if (!workspace || workspace_bytes < w.total) return MOSAIC_BSA_ERR_WORKSPACE;
