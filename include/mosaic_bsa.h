@@ -125,6 +125,29 @@ int mosaic_bsa_select(const mosaic_bsa_params *params, const void *q, const void
                       void *hip_stream);
 
 /*
+ * mosaic_bsa_select for callers that can neither allocate device memory nor
+ * hand over a workspace: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same results (bit
+ * for bit) as mosaic_bsa_select, but the selection workspace is a fixed array
+ * inside the library, MOSAIC_BSA_STATIC_SCRATCH_BYTES per GPU, that lives from
+ * the loading of the library to the end of the process; the call allocates
+ * and frees nothing.
+ *   - A problem whose selection workspace (mosaic_bsa_workspace_bytes(..,
+ *     OP_SELECT)) exceeds MOSAIC_BSA_STATIC_SCRATCH_BYTES is rejected with
+ *     MOSAIC_BSA_ERR_WORKSPACE before anything is enqueued.
+ *   - All calls on one GPU share that GPU's array: calls whose stream work can
+ *     overlap on one GPU race with each other.  Nothing in the array has to
+ *     start at zero (every part is written before it is read), so consecutive
+ *     calls on one stream need nothing between them.
+ *   - The first call on a device looks up the array's address
+ *     (hipGetSymbolAddress, with that device current); make it outside graph
+ *     capture.  The pooled tensors are not handed back to the caller.
+ */
+#define MOSAIC_BSA_STATIC_SCRATCH_BYTES (32u << 20)
+int mosaic_bsa_select_static(const mosaic_bsa_params *params, const void *q, const void *k,
+                             int32_t *sel_idx, void *hip_stream);
+
+/*
  * Block-sparse attention forward (fine-grained attention equation over the
  * union of the query block itself and its selected blocks, one softmax).
  *   q         in   device, [B, heads, N, D]

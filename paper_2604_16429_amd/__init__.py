@@ -4,7 +4,8 @@ from .binding import (BsaError, Params, library_path, load_library,  # noqa: F40
                       mosaic_bsa_bwd, mosaic_bsa_bwd_three_branch,
                       mosaic_bsa_check_selection, mosaic_bsa_fwd,
                       mosaic_bsa_fwd_three_branch,
-                      mosaic_bsa_probe_mfma, mosaic_bsa_select, mosaic_bsa_strerror,
+                      mosaic_bsa_probe_mfma, mosaic_bsa_select,
+                      mosaic_bsa_select_static, mosaic_bsa_strerror,
                       mosaic_bsa_three_branch_bwd_workspace_bytes,
                       mosaic_bsa_three_branch_workspace_bytes,
                       mosaic_bsa_workspace_bytes)

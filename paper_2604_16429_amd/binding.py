@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
         lib.mosaic_bsa_workspace_bytes.argtypes = [pp, i32]
         lib.mosaic_bsa_select.restype = i32
         lib.mosaic_bsa_select.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+        lib.mosaic_bsa_select_static.restype = i32
+        lib.mosaic_bsa_select_static.argtypes = [pp, vp, vp, vp, vp]
         lib.mosaic_bsa_fwd.restype = i32
         lib.mosaic_bsa_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.mosaic_bsa_bwd.restype = i32
@@ -156,6 +158,12 @@ def mosaic_bsa_select(params: Params, q, k, sel_idx, workspace, stream=None,
     _check(load_library().mosaic_bsa_select(
         ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(sel_idx), _ptr(workspace), wb,
         _stream(stream)))
+
+
+def mosaic_bsa_select_static(params: Params, q, k, sel_idx, stream=None) -> None:
+    cp = params.c_struct()
+    _check(load_library().mosaic_bsa_select_static(
+        ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(sel_idx), _stream(stream)))
 
 
 def mosaic_bsa_fwd(params: Params, q, k, v, sel_idx, out, lse=None,

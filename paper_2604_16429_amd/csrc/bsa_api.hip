@@ -5,7 +5,16 @@
 
 #include <math.h>
 
+#include <mutex>
+
 #include "bsa_launch.h"
+
+// Device memory of mosaic_bsa_select_static, which may not take a workspace from
+// its caller nor allocate one: every GPU the library runs on holds this array
+// from the moment the code object is loaded until the process ends.  In host
+// code the name is only a handle; the array's address on a device comes from
+// hipGetSymbolAddress (static_scratch() below).
+static __device__ __align__(256) unsigned char scratch[MOSAIC_BSA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -100,6 +109,52 @@ extern "C" size_t mosaic_bsa_workspace_bytes(const mosaic_bsa_params* params, in
     return 0;
 }
 
+namespace {
+
+// Pooling, block scores and top-n with the selection workspace at `workspace`
+// (select_workspace(c) bytes, 256-byte aligned, contents arbitrary: every part
+// is written before it is read).
+int select_impl(const Checked& c, const void* q, const void* k, int32_t* sel_idx, void* workspace,
+                hipStream_t stream)
+{
+    float* qbar = (float*)workspace;
+    float* kbar = (float*)((char*)workspace + pooled_bytes(c));
+    void* rest = (char*)workspace + 2 * pooled_bytes(c);
+    if (c.g.n_select > 0 && bsa::pool_select_overlaps(c.g.n_blocks))
+        return bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, rest, sel_idx, c.g, c.D,
+                                       c.BH, stream) == hipSuccess ? MOSAIC_BSA_OK
+                                                             : MOSAIC_BSA_ERR_LAUNCH;
+    if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    if (c.g.n_select == 0) return MOSAIC_BSA_OK;
+    if (bsa::launch_select(qbar, kbar, sel_idx, rest, c.g, c.D, c.BH, stream) != hipSuccess)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    return MOSAIC_BSA_OK;
+}
+
+// Address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_on_device[kMaxDevices];
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return MOSAIC_BSA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_on_device[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+            return MOSAIC_BSA_ERR_LAUNCH;
+        scratch_on_device[dev] = p;
+    }
+    *out = scratch_on_device[dev];
+    return MOSAIC_BSA_OK;
+}
+
+}  // namespace
+
 extern "C" int mosaic_bsa_select(const mosaic_bsa_params* params, const void* q, const void* k,
                                  int32_t* sel_idx, void* workspace, size_t workspace_bytes,
                                  void* hip_stream)
@@ -111,21 +166,23 @@ extern "C" int mosaic_bsa_select(const mosaic_bsa_params* params, const void* q,
     if (misaligned(q) || misaligned(k) || misaligned(workspace)) return MOSAIC_BSA_ERR_ALIGN;
     if (!workspace || workspace_bytes < select_workspace(c)) return MOSAIC_BSA_ERR_WORKSPACE;
     if (bsa::select_group_size(c.g.n_blocks, c.D) == 0) return MOSAIC_BSA_ERR_SHAPE;
+    return select_impl(c, q, k, sel_idx, workspace, (hipStream_t)hip_stream);
+}
 
-    hipStream_t stream = (hipStream_t)hip_stream;
-    float* qbar = (float*)workspace;
-    float* kbar = (float*)((char*)workspace + pooled_bytes(c));
-    void* scratch = (char*)workspace + 2 * pooled_bytes(c);
-    if (c.g.n_select > 0 && bsa::pool_select_overlaps(c.g.n_blocks))
-        return bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, scratch, sel_idx, c.g, c.D,
-                                       c.BH, stream) == hipSuccess ? MOSAIC_BSA_OK
-                                                             : MOSAIC_BSA_ERR_LAUNCH;
-    if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess)
-        return MOSAIC_BSA_ERR_LAUNCH;
-    if (c.g.n_select == 0) return MOSAIC_BSA_OK;
-    if (bsa::launch_select(qbar, kbar, sel_idx, scratch, c.g, c.D, c.BH, stream) != hipSuccess)
-        return MOSAIC_BSA_ERR_LAUNCH;
-    return MOSAIC_BSA_OK;
+extern "C" int mosaic_bsa_select_static(const mosaic_bsa_params* params, const void* q,
+                                        const void* k, int32_t* sel_idx, void* hip_stream)
+{
+    Checked c;
+    if (int rc = check_params(params, &c)) return rc;
+    if (!q || !k) return MOSAIC_BSA_ERR_NULL;
+    if (c.g.n_select > 0 && !sel_idx) return MOSAIC_BSA_ERR_NULL;
+    if (misaligned(q) || misaligned(k)) return MOSAIC_BSA_ERR_ALIGN;
+    if (bsa::select_group_size(c.g.n_blocks, c.D) == 0) return MOSAIC_BSA_ERR_SHAPE;
+    if (select_workspace(c) > (size_t)MOSAIC_BSA_STATIC_SCRATCH_BYTES)
+        return MOSAIC_BSA_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return select_impl(c, q, k, sel_idx, ws, (hipStream_t)hip_stream);
 }
 
 namespace {
@@ -465,7 +522,9 @@ extern "C" const char* mosaic_bsa_strerror(int code)
                "three-branch form)";
     case MOSAIC_BSA_ERR_HEAD_DIM: return "head_dim must be 32, 64 or 128";
     case MOSAIC_BSA_ERR_DTYPE: return "dtype must be MOSAIC_BSA_F32 or MOSAIC_BSA_BF16";
-    case MOSAIC_BSA_ERR_WORKSPACE: return "workspace is NULL or smaller than required";
+    case MOSAIC_BSA_ERR_WORKSPACE:
+        return "workspace is NULL or smaller than required (mosaic_bsa_select_static: the "
+               "problem needs more than MOSAIC_BSA_STATIC_SCRATCH_BYTES of selection workspace)";
     case MOSAIC_BSA_ERR_ALIGN: return "tensor base pointers must be 16-byte aligned";
     case MOSAIC_BSA_ERR_LAUNCH: return "HIP kernel launch failed";
     case MOSAIC_BSA_ERR_OP: return "operation not available";

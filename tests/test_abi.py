@@ -188,3 +188,25 @@ def test_selection_checker_arguments_are_checked_on_the_host():
     with pytest.raises(M.BsaError) as e:
         M.mosaic_bsa_check_selection(good(n_select=32), 0x1000, False, 0x1000, stream=0)
     assert e.value.code == -3                           # n = m only with the own block allowed
+
+
+def test_static_selection_checks_arguments_and_size_on_the_host():
+    """The entry point without a workspace argument: argument errors and a
+    problem that needs more than the library's fixed array are reported before
+    any GPU call is made."""
+    fake = 4096
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_select_static(good(), None, fake, fake, stream=0)
+    assert e.value.code == -1
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_select_static(good(), fake + 4, fake, fake, stream=0)
+    assert e.value.code == -7
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_select_static(good(head_dim=48), fake, fake, fake, stream=0)
+    assert e.value.code == -4
+    big = good(batch=24, heads=16, grid_h=120, grid_w=240, head_dim=64, n_select=16,
+               dtype=binding.BF16)
+    assert M.mosaic_bsa_workspace_bytes(big, binding.OP_SELECT) > 32 << 20
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_select_static(big, fake, fake, fake, stream=0)
+    assert e.value.code == -6
