@@ -78,7 +78,7 @@ bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// pooled q | pooled k | ranking keys (only where the selection needs them)
+// pooled q | pooled k | the ranking's channel-interleaved copy of the pooled k
 size_t pooled_bytes(const Checked& c)
 {
     return align_up((size_t)c.BH * c.g.n_blocks * c.D * sizeof(float));
@@ -120,16 +120,12 @@ int select_impl(const Checked& c, const void* q, const void* k, int32_t* sel_idx
     float* qbar = (float*)workspace;
     float* kbar = (float*)((char*)workspace + pooled_bytes(c));
     void* rest = (char*)workspace + 2 * pooled_bytes(c);
-    if (c.g.n_select > 0 && bsa::pool_select_overlaps(c.g.n_blocks))
-        return bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, rest, sel_idx, c.g, c.D,
-                                       c.BH, stream) == hipSuccess ? MOSAIC_BSA_OK
-                                                             : MOSAIC_BSA_ERR_LAUNCH;
-    if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) != hipSuccess)
-        return MOSAIC_BSA_ERR_LAUNCH;
-    if (c.g.n_select == 0) return MOSAIC_BSA_OK;
-    if (bsa::launch_select(qbar, kbar, sel_idx, rest, c.g, c.D, c.BH, stream) != hipSuccess)
-        return MOSAIC_BSA_ERR_LAUNCH;
-    return MOSAIC_BSA_OK;
+    const hipError_t e =
+        c.g.n_select > 0
+            ? bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, rest, sel_idx, c.g, c.D, c.BH,
+                                      stream)
+            : bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream);
+    return e == hipSuccess ? MOSAIC_BSA_OK : MOSAIC_BSA_ERR_LAUNCH;
 }
 
 // Address of `scratch` on the current device, looked up once per device.
@@ -304,16 +300,9 @@ extern "C" int mosaic_bsa_fwd_three_branch(const mosaic_bsa_params* params, int3
 
     // compression (pooled q, k, v), the coarse branch, and the ranking it shares
     // with the selection branch
-    if (bsa::pool_select_overlaps(c.g.n_blocks)) {
-        if (bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, ws + w.keys, sel_idx, c.g, c.D,
-                                    c.BH, stream) != hipSuccess)
-            return MOSAIC_BSA_ERR_LAUNCH;
-    } else if (bsa::launch_pool(c.is_bf16, q, k, qbar, kbar, c.g, c.D, c.BH, stream) !=
-                   hipSuccess ||
-               bsa::launch_select(qbar, kbar, sel_idx, ws + w.keys, c.g, c.D, c.BH, stream) !=
-                   hipSuccess) {
+    if (bsa::launch_pool_select(c.is_bf16, q, k, qbar, kbar, ws + w.keys, sel_idx, c.g, c.D, c.BH,
+                                stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
-    }
     if (bsa::launch_pool_one(c.is_bf16, v, vbar, c.g, c.D, c.BKV, stream) != hipSuccess ||
         bsa::launch_coarse(qbar, kbar,
                            bsa::select_interleaves_keys(c.g.n_blocks) ? (const float*)(ws + w.keys)

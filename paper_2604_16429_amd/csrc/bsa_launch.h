@@ -25,19 +25,14 @@ hipError_t launch_check_selection(const int32_t* sel_idx, int32_t* n_bad, const 
 hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom& g, int D,
                            int64_t slices, hipStream_t stream);
 
-// `scratch`: device memory of select_scratch_bytes(...) bytes (BKV = batch *
-// kv_heads): for m <= 512 a second copy of the pooled keys, per slice
-// [D/4][m][4], for 512 < m <= 4096 the global matrix of ranking keys, else none.
+// Pooling of Q and K, block scores and top-n as one sequence of launches in
+// which the pooling of one part of the batch runs beside the ranking of the part
+// before.  The scores of a query block stay in LDS; `scratch` is device memory
+// of select_scratch_bytes(...) bytes (BKV = batch * kv_heads): a second copy of
+// the pooled keys, per slice [D/4][m][4], which the ranking's threads (one key
+// block each) read as consecutive 16-byte groups and launch_pool_select leaves
+// there (select_interleaves_keys(m)).
 size_t select_scratch_bytes(int m, int D, int64_t BH, int64_t BKV);
-hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, void* scratch,
-                         const Geom& g, int D, int64_t BH, hipStream_t stream);
-
-// launch_pool + launch_select as one sequence of launches in which the pooling
-// of one part of the batch runs beside the ranking of the part before (only
-// where pool_select_overlaps(m): the ranking that needs no scratch).
-bool pool_select_overlaps(int m);
-// Whether launch_pool_select leaves the channel-interleaved copy of the pooled
-// keys ([B*kv_heads][D/4][m][4]) at the start of its scratch.
 bool select_interleaves_keys(int m);
 hipError_t launch_pool_select(bool is_bf16, const void* q, const void* k, float* qbar,
                               float* kbar, void* scratch, int32_t* sel_idx, const Geom& g, int D,

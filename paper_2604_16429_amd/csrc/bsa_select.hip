@@ -5,8 +5,9 @@
 //                  rank-equivalent raw dot-product form) and the top-n key
 //                  blocks of every query block (Selection paragraph);
 //   pool_select_kernel  both in one launch: the pooling of one part of the
-//                  batch beside the ranking of the part pooled just before;
-//   scores_kernel, topn_kernel  the ranking for 512 < m <= 4096 blocks.
+//                  batch beside the ranking of the part pooled just before.
+// The scores of a query block live in LDS between the two phases of
+// select_block and nowhere else: nothing of the m x m score matrix reaches HBM.
 //
 // The arithmetic is pinned so that the emitted indices are reproducible bit
 // for bit by a scalar loop: pooled sums are fp32 adds in in-tile row-major
@@ -157,8 +158,88 @@ __device__ __forceinline__ void sort8_desc(uint64_t (&a)[9])
 #undef BSA_CE
 }
 
-// Candidates a lane keeps in registers in the top-n phase (m <= 64 * kSlots).
+// Candidates a lane keeps in registers in the top-n phase: 8 for m <= 512
+// (sorted once), 64 for 512 < m <= 4096 (best of every group of 8 cached).
 constexpr int kSlots = 8;
+constexpr int kBigSlots = 64;
+
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+
+// One group of 8 candidate slots of a lane (a vector value, so that it lives in
+// registers): remove slot `which` (0..7; 8 = none), then re-derive the group's
+// best key and its slot.  Equal keys keep the lower slot, i.e. the smaller block
+// index.
+__device__ __forceinline__ void regroup(u32x8& grp, uint32_t& gbest, uint32_t& gslot,
+                                        uint32_t which)
+{
+#pragma unroll
+    for (int u = 0; u < 8; ++u) grp[u] = which == (uint32_t)u ? 0u : grp[u];
+    uint32_t b = grp[0], sl = 0;
+#pragma unroll
+    for (int u = 1; u < 8; ++u)
+        if (grp[u] > b) { b = grp[u]; sl = (uint32_t)u; }
+    gbest = b;
+    gslot = sl;
+}
+
+// Top-n of one row of m <= 4096 ranking keys (in LDS) by one wavefront.  Lane l
+// keeps the candidates j == l (mod 64) in registers, slot j / 64, with the best
+// of every group of 8 slots cached; per round: wave-wide max of the lanes' best
+// keys, the winner is the lane holding it (smallest block index among equal
+// keys), and only the winner's group of 8 is rescanned.
+__device__ __forceinline__ void topn_of_row_in_registers(const uint32_t* keys,
+                                                         int32_t* __restrict__ dst, int m, int n,
+                                                         int lane)
+{
+    u32x8 g0, g1, g2, g3, g4, g5, g6, g7;
+    uint32_t gbest[8], gslot[8];
+#define BSA_LOAD_GROUP(GI, GRP)                                                                 \
+    _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                              \
+        const int j = lane + 64 * (GI * 8 + u);                                                  \
+        GRP[u] = j < m ? keys[j] : 0u;                                                           \
+    }                                                                                            \
+    regroup(GRP, gbest[GI], gslot[GI], 8u);
+    BSA_LOAD_GROUP(0, g0) BSA_LOAD_GROUP(1, g1) BSA_LOAD_GROUP(2, g2) BSA_LOAD_GROUP(3, g3)
+    BSA_LOAD_GROUP(4, g4) BSA_LOAD_GROUP(5, g5) BSA_LOAD_GROUP(6, g6) BSA_LOAD_GROUP(7, g7)
+#undef BSA_LOAD_GROUP
+    auto lane_best = [&](uint32_t& best, uint32_t& best_j) {
+        best = gbest[0]; uint32_t slot = gslot[0];
+#pragma unroll
+        for (int gi = 1; gi < 8; ++gi)
+            if (gbest[gi] > best) { best = gbest[gi]; slot = 8u * gi + gslot[gi]; }
+        best_j = best ? (uint32_t)lane + 64u * slot : 0xffffffffu;
+    };
+    uint32_t best, best_j;
+    lane_best(best, best_j);
+    uint32_t picks = 0;
+    for (int t = 0; t < n; ++t) {
+        const uint32_t top = wave_umax(best);
+        const uint64_t holders = __builtin_amdgcn_ballot_w64(best == top);
+        uint32_t win;
+        if (__builtin_expect(__builtin_popcountll(holders) == 1, 1))
+            win = __builtin_amdgcn_readlane(best_j, (int)__builtin_ctzll(holders));
+        else
+            win = wave_umin(best == top ? best_j : 0xffffffffu);
+        picks = lane == (t & 63) ? win : picks;          // lane t % 64 keeps pick t
+        if ((win & 63u) == (uint32_t)lane) {
+            const uint32_t slot = win >> 6, which = slot & 7u;   // wave-uniform values
+            switch (slot >> 3) {
+            case 0: regroup(g0, gbest[0], gslot[0], which); break;
+            case 1: regroup(g1, gbest[1], gslot[1], which); break;
+            case 2: regroup(g2, gbest[2], gslot[2], which); break;
+            case 3: regroup(g3, gbest[3], gslot[3], which); break;
+            case 4: regroup(g4, gbest[4], gslot[4], which); break;
+            case 5: regroup(g5, gbest[5], gslot[5], which); break;
+            case 6: regroup(g6, gbest[6], gslot[6], which); break;
+            default: regroup(g7, gbest[7], gslot[7], which); break;
+            }
+            lane_best(best, best_j);
+        }
+        if ((t & 63) == 63 || t == n - 1) {
+            if (lane <= (t & 63)) dst[(t & ~63) + lane] = (int32_t)picks;
+        }
+    }
+}
 
 // One workgroup of 256 threads ranks G consecutive query blocks of one
 // (batch, head).
@@ -172,8 +253,10 @@ constexpr int kSlots = 8;
 //            repeated arg-max over the lanes' best remaining candidates
 //            (j == lane mod 64): a wave-wide max of the scores, then, only if
 //            several lanes hold it, a wave-wide min of their block indices.
-// LDS: G*m u32 (ranking keys).
-template <int D>
+// LDS: G*m u32 (ranking keys).  BIG: the variant for 512 < m <= 4096, whose
+// second phase keeps 64 candidates per lane (a kernel of its own: its register
+// count must not cost the common case its occupancy).
+template <int D, bool BIG>
 __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
                                              const float* __restrict__ kbar,
                                              const float* __restrict__ kbar_il,
@@ -196,8 +279,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
 
     // ---- phase 1: scores.  The pooled queries are wave-uniform and are fetched
     // with scalar loads straight into the fma's scalar operand.
-    for (int j = threadIdx.x; j < m; j += blockDim.x) {
-        float kr[D];
+    auto load_key = [&](int j, float (&kr)[D]) {
         // the interleaved copy where there is one, else the key block's row
         const float4* ksrc = kbar_il ? (const float4*)kbar_il + j
                                      : (const float4*)(kbar + (int64_t)j * D);
@@ -208,12 +290,41 @@ __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
             kr[4 * d4 + 0] = v.x; kr[4 * d4 + 1] = v.y;
             kr[4 * d4 + 2] = v.z; kr[4 * d4 + 3] = v.w;
         }
+    };
+    auto put_key = [&](int r, int j, float acc) {
+        key_s[r * m + j] = (j == i0 + r && !g.own_is_candidate) ? 0u : rank_key(acc);
+    };
+    int j = threadIdx.x;
+    if constexpr (BIG && D <= 64) {
+        // Two key blocks per thread at a time: with this many blocks the LDS rows
+        // leave one workgroup per CU, i.e. one wavefront per SIMD, and the two
+        // independent chains (same scalar operand) hide the latency of one.
+        for (; j + (int)blockDim.x < m; j += 2 * (int)blockDim.x) {
+            float ka[D], kb[D];
+            load_key(j, ka);
+            load_key(j + (int)blockDim.x, kb);
+            for (int r = 0; r < rows; ++r) {
+                const float* __restrict__ qrow = qbar + r * D;
+                float a = 0.0f, b = 0.0f;
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    a = __builtin_fmaf(qrow[d], ka[d], a);
+                    b = __builtin_fmaf(qrow[d], kb[d], b);
+                }
+                put_key(r, j, a);
+                put_key(r, j + (int)blockDim.x, b);
+            }
+        }
+    }
+    for (; j < m; j += blockDim.x) {
+        float kr[D];
+        load_key(j, kr);
         for (int r = 0; r < rows; ++r) {
             const float* __restrict__ qrow = qbar + r * D;
             float acc = 0.0f;
 #pragma unroll
             for (int d = 0; d < D; ++d) acc = __builtin_fmaf(qrow[d], kr[d], acc);
-            key_s[r * m + j] = (j == i0 + r && !g.own_is_candidate) ? 0u : rank_key(acc);
+            put_key(r, j, acc);
         }
     }
     __syncthreads();
@@ -223,6 +334,10 @@ __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
     for (int r = wave; r < rows; r += (int)(blockDim.x >> 6)) {
         uint32_t* keys = key_s + r * m;
         int32_t* dst = sel_idx + ((bh_idx * m) + i0 + r) * n;
+        if constexpr (BIG) {
+            topn_of_row_in_registers(keys, dst, m, n, lane);
+            continue;
+        }
         if (m <= 64 * kSlots) {
             // Candidates j == lane (mod 64) live in registers as composites
             // (key << 32 | ~j), which are all distinct and order the
@@ -300,7 +415,7 @@ __device__ __forceinline__ void select_block(const float* __restrict__ qbar,
 // The pooled means are passed twice: written through qbar_w / kbar_w / kbar_il_w
 // (the part being pooled), read through qbar_r / kbar_r / kbar_il_r (the part
 // being ranked).
-template <typename T, int VEC, int D>
+template <typename T, int VEC, int D, bool BIG>
 __global__ __launch_bounds__(256) void pool_select_kernel(
     const T* __restrict__ q, const T* __restrict__ k, float* __restrict__ qbar_w,
     float* __restrict__ kbar_w, float* __restrict__ kbar_il_w, const float* __restrict__ qbar_r,
@@ -310,149 +425,13 @@ __global__ __launch_bounds__(256) void pool_select_kernel(
     uint32_t n_pool_blocks, uint32_t n_poolers, uint32_t select_first)
 {
     if (blockIdx.x >= n_poolers) {
-        select_block<D>(qbar_r, kbar_r, kbar_il_r, sel_idx, g, G,
+        select_block<D, BIG>(qbar_r, kbar_r, kbar_il_r, sel_idx, g, G,
                         select_first + (blockIdx.x - n_poolers));
         return;
     }
     for (uint32_t v = blockIdx.x; v < n_pool_blocks; v += n_poolers)
         pool_block<T, VEC>(q, k, qbar_w, kbar_w, kbar_il_w, g, D, pool_q_first, pool_n_q, pool_k_first,
                            wgs_per_slice, v);
-}
-
-// ---------------------------------------------------------------------------
-// Many blocks (512 < m <= 4096): the ranking keys of a row no longer fit the
-// registers of the fused kernel and its LDS footprint leaves one workgroup per
-// CU.  Two kernels instead: the scores of R query blocks against 256 key blocks
-// per workgroup, ranking keys written to a global scratch matrix [B*h, m, m]
-// (same pinned fma chain, same keys), then one wavefront per row extracts the n
-// best from registers.
-// ---------------------------------------------------------------------------
-constexpr int kScoreRows = 32;          // query blocks per scores workgroup
-constexpr int kBigSlots = 64;           // candidates per lane in topn_kernel: m <= 4096
-
-template <int D>
-__global__ __launch_bounds__(256) void scores_kernel(const float* __restrict__ qbar,
-                                                     const float* __restrict__ kbar,
-                                                     uint32_t* __restrict__ keys, Geom g)
-{
-    __shared__ __attribute__((aligned(16))) float q_s[kScoreRows * D];
-    const int m = g.n_blocks;
-    const int row_groups = (m + kScoreRows - 1) / kScoreRows, key_chunks = (m + 255) / 256;
-    // blockIdx.x = (batch*head * row_groups + row group) * key_chunks + key chunk
-    const int kc = blockIdx.x % key_chunks;
-    const int64_t t = blockIdx.x / key_chunks;
-    const int i0 = (int)(t % row_groups) * kScoreRows;
-    const int64_t bh_idx = t / row_groups;
-    const int rows = min(kScoreRows, m - i0);
-    qbar += (bh_idx * m + i0) * D;
-    kbar += kv_slice_of(g, bh_idx) * m * D;
-    keys += (bh_idx * m + i0) * (int64_t)m;
-
-    for (int e = threadIdx.x; e < rows * D; e += blockDim.x) q_s[e] = qbar[e];
-    __syncthreads();
-
-    const int j = kc * 256 + (int)threadIdx.x;
-    if (j >= m) return;
-    float kr[D];
-    const float4* krow = (const float4*)(kbar + (int64_t)j * D);
-#pragma unroll
-    for (int d4 = 0; d4 < D / 4; ++d4) {
-        const float4 v = krow[d4];
-        kr[4 * d4 + 0] = v.x; kr[4 * d4 + 1] = v.y;
-        kr[4 * d4 + 2] = v.z; kr[4 * d4 + 3] = v.w;
-    }
-    for (int r = 0; r < rows; ++r) {
-        const float4* qrow = (const float4*)(q_s + r * D);
-        float acc = 0.0f;
-#pragma unroll
-        for (int d4 = 0; d4 < D / 4; ++d4) {
-            const float4 qv = qrow[d4];
-            acc = __builtin_fmaf(qv.x, kr[4 * d4 + 0], acc);
-            acc = __builtin_fmaf(qv.y, kr[4 * d4 + 1], acc);
-            acc = __builtin_fmaf(qv.z, kr[4 * d4 + 2], acc);
-            acc = __builtin_fmaf(qv.w, kr[4 * d4 + 3], acc);
-        }
-        keys[(int64_t)r * m + j] = (j == i0 + r && !g.own_is_candidate) ? 0u : rank_key(acc);
-    }
-}
-
-// Group GI of 8 register slots: remove slot `which` (0..7), then re-derive the
-// group's best key and its slot.  Equal keys keep the lower slot, i.e. the
-// smaller block index.
-template <int GI>
-__device__ __forceinline__ void regroup(uint32_t (&kreg)[kBigSlots], uint32_t (&gbest)[8],
-                                        uint32_t (&gslot)[8], uint32_t which)
-{
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-        if (which == (uint32_t)u) kreg[GI * 8 + u] = 0u;
-    uint32_t b = kreg[GI * 8], sl = 0;
-#pragma unroll
-    for (int u = 1; u < 8; ++u)
-        if (kreg[GI * 8 + u] > b) { b = kreg[GI * 8 + u]; sl = (uint32_t)u; }
-    gbest[GI] = b;
-    gslot[GI] = (uint32_t)(GI * 8) + sl;
-}
-
-// One wavefront per query block (four per workgroup).  Lane l keeps the
-// candidates j == l (mod 64) in registers, slot j / 64, with the best of every
-// group of 8 slots cached; per round: wave-wide max of the lanes' best keys,
-// the winner is the lane holding it (smallest block index among equal keys),
-// and only the winner's group of 8 is rescanned.
-__global__ __launch_bounds__(256) void topn_kernel(const uint32_t* __restrict__ keys,
-                                                   int32_t* __restrict__ sel_idx, Geom g,
-                                                   int64_t rows_total)
-{
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows_total) return;                   // whole wavefront; no barriers below
-    const int m = g.n_blocks, n = g.n_select;
-    const uint32_t* krow = keys + row * m;
-    int32_t* dst = sel_idx + row * n;
-
-    uint32_t kreg[kBigSlots], gbest[8], gslot[8];
-#pragma unroll
-    for (int t = 0; t < kBigSlots; ++t) {
-        const int j = lane + 64 * t;
-        kreg[t] = j < m ? krow[j] : 0u;
-    }
-    regroup<0>(kreg, gbest, gslot, 8u); regroup<1>(kreg, gbest, gslot, 8u);
-    regroup<2>(kreg, gbest, gslot, 8u); regroup<3>(kreg, gbest, gslot, 8u);
-    regroup<4>(kreg, gbest, gslot, 8u); regroup<5>(kreg, gbest, gslot, 8u);
-    regroup<6>(kreg, gbest, gslot, 8u); regroup<7>(kreg, gbest, gslot, 8u);
-    auto lane_best = [&](uint32_t& best, uint32_t& best_j) {
-        best = gbest[0]; uint32_t slot = gslot[0];
-#pragma unroll
-        for (int gi = 1; gi < 8; ++gi)
-            if (gbest[gi] > best) { best = gbest[gi]; slot = gslot[gi]; }
-        best_j = best ? (uint32_t)lane + 64u * slot : 0xffffffffu;
-    };
-    uint32_t best, best_j;
-    lane_best(best, best_j);
-    for (int t = 0; t < n; ++t) {
-        const uint32_t top = wave_umax(best);
-        const uint64_t holders = __builtin_amdgcn_ballot_w64(best == top);
-        uint32_t win;
-        if (__builtin_expect(__builtin_popcountll(holders) == 1, 1))
-            win = __builtin_amdgcn_readlane(best_j, (int)__builtin_ctzll(holders));
-        else
-            win = wave_umin(best == top ? best_j : 0xffffffffu);
-        if (lane == 0) dst[t] = (int32_t)win;
-        if ((win & 63u) == (uint32_t)lane) {
-            const uint32_t slot = win >> 6, which = slot & 7u;   // wave-uniform values
-            switch (slot >> 3) {
-            case 0: regroup<0>(kreg, gbest, gslot, which); break;
-            case 1: regroup<1>(kreg, gbest, gslot, which); break;
-            case 2: regroup<2>(kreg, gbest, gslot, which); break;
-            case 3: regroup<3>(kreg, gbest, gslot, which); break;
-            case 4: regroup<4>(kreg, gbest, gslot, which); break;
-            case 5: regroup<5>(kreg, gbest, gslot, which); break;
-            case 6: regroup<6>(kreg, gbest, gslot, which); break;
-            default: regroup<7>(kreg, gbest, gslot, which); break;
-            }
-            lane_best(best, best_j);
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -509,7 +488,12 @@ static size_t select_lds_bytes(int G, int m, int D)
 
 int select_group_size(int m, int D)
 {
-    // the largest G in [1, 8] whose LDS footprint fits; 0 if even G = 1 does not
+    // the largest G in [1, 8] whose LDS footprint fits, and fits twice where
+    // that is possible with G >= 4 (two workgroups per CU cover each other's
+    // loads, and a pooling workgroup fits beside a ranking one); 0 if even
+    // G = 1 does not fit
+    for (int G = 8; G >= 4; G >>= 1)
+        if (2 * select_lds_bytes(G, m, D) <= kSelectLdsBudget) return G;
     for (int G = 8; G >= 1; G >>= 1)
         if (select_lds_bytes(G, m, D) <= kSelectLdsBudget) return G;
     return 0;
@@ -552,46 +536,11 @@ hipError_t launch_pool_one(bool is_bf16, const void* x, float* xbar, const Geom&
     return hipGetLastError();
 }
 
-static bool two_kernel_path(int m) { return m > 64 * kSlots && m <= 64 * kBigSlots; }
-
 size_t select_scratch_bytes(int m, int D, int64_t BH, int64_t BKV)
 {
-    // the two-kernel path keeps the ranking keys of every row in global memory,
-    // the fused ranking of m <= 512 reads a second, interleaved copy of the pooled keys
-    if (two_kernel_path(m)) return (size_t)BH * (size_t)m * (size_t)m * 4;
-    return m <= 64 * kSlots ? (size_t)BKV * (size_t)m * (size_t)D * 4 : 0;
-}
-
-template <int D>
-static hipError_t launch_select_t(const float* qbar, const float* kbar, int32_t* sel_idx,
-                                  uint32_t* keys, const Geom& g, int64_t BH, hipStream_t stream)
-{
-    if (two_kernel_path(g.n_blocks)) {
-        const int m = g.n_blocks;
-        const int64_t wgs = BH * ((m + kScoreRows - 1) / kScoreRows) * ((m + 255) / 256);
-        if (!keys || wgs >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((scores_kernel<D>), dim3((unsigned)wgs), dim3(256), 0, stream, qbar,
-                           kbar, keys, g);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        const int64_t rows_total = BH * m;
-        hipLaunchKernelGGL(topn_kernel, dim3((unsigned)((rows_total + 3) / 4)), dim3(256), 0,
-                           stream, keys, sel_idx, g, rows_total);
-        return hipGetLastError();
-    }
-    return hipErrorInvalidValue;     // every other m is ranked by launch_pool_select
-}
-
-hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx, void* scratch,
-                         const Geom& g, int D, int64_t BH, hipStream_t stream)
-{
-    uint32_t* keys = (uint32_t*)scratch;
-    switch (D) {
-    case 32: return launch_select_t<32>(qbar, kbar, sel_idx, keys, g, BH, stream);
-    case 64: return launch_select_t<64>(qbar, kbar, sel_idx, keys, g, BH, stream);
-    case 128: return launch_select_t<128>(qbar, kbar, sel_idx, keys, g, BH, stream);
-    }
-    return hipErrorInvalidValue;
+    (void)BH;
+    // the ranking reads a second, channel-interleaved copy of the pooled keys
+    return (size_t)BKV * (size_t)m * (size_t)D * 4;
 }
 
 #ifndef BSA_SELECT_PARTS
@@ -603,11 +552,9 @@ hipError_t launch_select(const float* qbar, const float* kbar, int32_t* sel_idx,
 // pooling workgroups that stay resident beside the ranking (one per CU)
 constexpr int64_t kPoolers = BSA_POOLERS;
 
-bool pool_select_overlaps(int m) { return !two_kernel_path(m); }
+bool select_interleaves_keys(int m) { (void)m; return true; }
 
-bool select_interleaves_keys(int m) { return m <= 64 * kSlots; }
-
-template <typename T, int VEC, int D>
+template <typename T, int VEC, int D, bool BIG>
 static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar, float* kbar,
                                        float* kbar_il, int32_t* sel_idx, const Geom& g,
                                        int64_t BH, hipStream_t stream)
@@ -621,7 +568,7 @@ static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute((const void*)pool_select_kernel<T, VEC, D>,
+        hipError_t e = hipFuncSetAttribute((const void*)pool_select_kernel<T, VEC, D, BIG>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kSelectLdsBudget);
         if (e != hipSuccess) return e;
@@ -652,7 +599,7 @@ static hipError_t launch_pool_select_t(const void* q, const void* k, float* qbar
         if (n_pool >= ((int64_t)1 << 31) || n_poolers + n_sel >= ((int64_t)1 << 31) ||
             sel_first + n_sel >= ((int64_t)1 << 32))
             return hipErrorInvalidValue;
-        hipLaunchKernelGGL((pool_select_kernel<T, VEC, D>), dim3((unsigned)(n_poolers + n_sel)),
+        hipLaunchKernelGGL((pool_select_kernel<T, VEC, D, BIG>), dim3((unsigned)(n_poolers + n_sel)),
                            dim3(256), lds, stream, (const T*)q, (const T*)k, qbar, kbar, kbar_il,
                            (const float*)qbar, (const float*)kbar, (const float*)kbar_il, sel_idx,
                            g, G, pq0, pnq, pk0,
@@ -668,20 +615,20 @@ hipError_t launch_pool_select(bool is_bf16, const void* q, const void* k, float*
                               float* kbar, void* scratch, int32_t* sel_idx, const Geom& g, int D,
                               int64_t BH, hipStream_t stream)
 {
-    // the interleaved copy of the pooled keys (m <= 512)
-    float* il = g.n_blocks <= 64 * kSlots ? (float*)scratch : nullptr;
-    if (g.n_blocks <= 64 * kSlots && !il) return hipErrorInvalidValue;
+    // the channel-interleaved copy of the pooled keys
+    const int m = g.n_blocks;
+    float* il = (float*)scratch;
+    if (!il) return hipErrorInvalidValue;
+    const bool big = m > 64 * kSlots && m <= 64 * kBigSlots;
+#define BSA_PS(T, VEC, D_)                                                                        \
+    (big ? launch_pool_select_t<T, VEC, D_, true>(q, k, qbar, kbar, il, sel_idx, g, BH, stream)   \
+         : launch_pool_select_t<T, VEC, D_, false>(q, k, qbar, kbar, il, sel_idx, g, BH, stream))
     switch (D) {
-    case 32:
-        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 32>(q, k, qbar, kbar, il, sel_idx, g, BH, stream)
-                       : launch_pool_select_t<float, 4, 32>(q, k, qbar, kbar, il, sel_idx, g, BH, stream);
-    case 64:
-        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 64>(q, k, qbar, kbar, il, sel_idx, g, BH, stream)
-                       : launch_pool_select_t<float, 4, 64>(q, k, qbar, kbar, il, sel_idx, g, BH, stream);
-    case 128:
-        return is_bf16 ? launch_pool_select_t<uint16_t, 8, 128>(q, k, qbar, kbar, il, sel_idx, g, BH, stream)
-                       : launch_pool_select_t<float, 4, 128>(q, k, qbar, kbar, il, sel_idx, g, BH, stream);
+    case 32: return is_bf16 ? BSA_PS(uint16_t, 8, 32) : BSA_PS(float, 4, 32);
+    case 64: return is_bf16 ? BSA_PS(uint16_t, 8, 64) : BSA_PS(float, 4, 64);
+    case 128: return is_bf16 ? BSA_PS(uint16_t, 8, 128) : BSA_PS(float, 4, 128);
     }
+#undef BSA_PS
     return hipErrorInvalidValue;
 }
 
