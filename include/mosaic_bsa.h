@@ -177,8 +177,11 @@ int mosaic_bsa_fwd(const mosaic_bsa_params *params, const void *q, const void *k
  *                            heads that share a key/value head)
  *   workspace                device scratch of
  *                            mosaic_bsa_workspace_bytes(.., OP_BWD) bytes; on
- *                            return its first half holds delta_l = dout_l . out_l,
- *                            fp32 [B, heads, N] (the second half is scratch).
+ *                            return its start holds delta_l = dout_l . out_l,
+ *                            fp32 [B, heads, N] (the rest is scratch: the
+ *                            log-sum-exps in base 2 and the reverse map of the
+ *                            selection, one bit per (query slice, key block,
+ *                            query block)).
  * dk/dv of a key block are reduced over the query blocks that attend to it in
  * a fixed order (no floating-point atomics): results are run-to-run identical.
  */

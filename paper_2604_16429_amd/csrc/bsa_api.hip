@@ -89,10 +89,16 @@ size_t select_workspace(const Checked& c)
     return 2 * pooled_bytes(c) + align_up(bsa::select_scratch_bytes(c.g.n_blocks, c.D, c.BH, c.BKV));
 }
 
+// delta | lse * log2(e) | connection map (the last two: matrix-core path only)
+size_t bwd_rows_bytes(const Checked& c)
+{
+    return align_up((size_t)c.BH * (size_t)c.g.n_tokens * sizeof(float));
+}
+
 size_t bwd_workspace(const Checked& c)
 {
-    // delta, then lse * log2(e) (the second half is used by the matrix-core path)
-    return 2 * align_up((size_t)c.BH * (size_t)c.g.n_tokens * sizeof(float));
+    return 2 * bwd_rows_bytes(c) +
+           align_up((size_t)bsa::bwd_connection_words(c.g.n_blocks, c.BH) * sizeof(uint32_t));
 }
 
 }  // namespace
@@ -337,10 +343,11 @@ hipError_t backward(const Checked& c, const bsa::Geom& g, const void* q, const v
                     hipStream_t stream)
 {
     float* delta = (float*)scratch;
-    float* lse2 = (float*)((char*)scratch + bwd_workspace(c) / 2);
+    float* lse2 = (float*)((char*)scratch + bwd_rows_bytes(c));
+    uint32_t* conn = (uint32_t*)((char*)scratch + 2 * bwd_rows_bytes(c));
     return bsa::bwd_mfma_supported(c.is_bf16, g, c.D)
-               ? bsa::launch_bwd_mfma(q, k, v, out, lse, dout, lists, dq, dk, dv, delta, lse2, g,
-                                      c.D, c.BH, stream)
+               ? bsa::launch_bwd_mfma(q, k, v, out, lse, dout, lists, dq, dk, dv, delta, lse2,
+                                      conn, g, c.D, c.BH, stream)
                : bsa::launch_bwd(c.is_bf16, q, k, v, out, lse, dout, lists, dq, dk, dv, delta, g,
                                  c.D, c.BH, stream);
 }

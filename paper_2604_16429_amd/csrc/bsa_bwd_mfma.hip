@@ -460,7 +460,7 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
                                           const uint16_t* __restrict__ dout,
                                           const float* __restrict__ lse2,
                                           const float* __restrict__ delta,
-                                          const int32_t* __restrict__ sel_idx,
+                                          const uint32_t* __restrict__ conn,
                                           uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
                                           const Geom& g, uint32_t n_units)
 {
@@ -478,8 +478,9 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int n = g.n_select, m = g.n_blocks;
+    const int m = g.n_blocks;
     const int subs = g.block_tokens / 64;
+    const int words = (m + 31) >> 5;               // of a key block's row of the connection map
 
     // workgroup -> (key/value slice, key block), slices dealt to the 8 XCDs
     // whole; the query slices that share the key/value slice are consecutive
@@ -534,7 +535,7 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
     // order within each: the summation order is fixed
     for (int gq = 0; gq < g.kv_group; ++gq) {
     const int64_t bh_idx = bh_first + gq;
-    const int32_t* sel_bh = sel_idx + bh_idx * (int64_t)m * n;
+    const uint32_t* conn_row = conn + (bh_idx * (int64_t)m + j) * words;
     const __amdgpu_buffer_rsrc_t q_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(q + bh_idx * g.n_tokens * D), 0, slice_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -555,15 +556,11 @@ __device__ __forceinline__ void dkdv_body(const uint16_t* __restrict__ q,
     };
 
     for (int i0 = 0; i0 < m; i0 += SCAN) {
-        // ---- which of the query blocks i0 .. i0+SCAN-1 attend to block j?
-        // ascending order, so the summation order below is fixed
+        // ---- which of the query blocks i0 .. i0+SCAN-1 attend to block j?  One
+        // bit each in the connection map; ascending order, so the summation
+        // order below is fixed
         const int i_mine = i0 + (int)threadIdx.x;
-        bool hit = false;
-        if (i_mine < m) {
-            hit = i_mine == j && !g.list_only;    // list-only mode: the lists say it all
-            const int32_t* row = sel_bh + (int64_t)i_mine * n;
-            for (int r = 0; r < n; ++r) hit |= row[r] == j;
-        }
+        const bool hit = i_mine < m && ((conn_row[i_mine >> 5] >> (i_mine & 31)) & 1u) != 0;
         const uint64_t mask = __builtin_amdgcn_ballot_w64(hit);
         __syncthreads();                      // previous round's list and tiles fully consumed
         if (lane == 0) wave_cnt[wave] = __builtin_popcountll(mask);
@@ -705,6 +702,40 @@ __global__ __launch_bounds__(256) void bwd_mfma_prep_kernel(const uint16_t* __re
     }
 }
 
+// The reverse map of the selection ("the query blocks connected to a key/value
+// block", Appendix, kernel design paragraph) as a bit matrix: bit i of row
+// [query slice][key block j] says that query block i attends to block j.  One
+// thread per (query slice, query block) sets the bits of its row of sel_idx
+// (and its own block's, unless only the lists count) with integer atomic ORs:
+// the final state does not depend on their order.  A dK/dV workgroup then reads
+// its m bits instead of scanning all m * n entries of the slice, and walking
+// the set bits upwards is the fixed summation order.
+__global__ __launch_bounds__(256) void bwd_connect_clear_kernel(uint32_t* __restrict__ conn,
+                                                                int64_t n_words)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n_words) conn[t] = 0u;
+}
+
+__global__ __launch_bounds__(256) void bwd_connect_kernel(const int32_t* __restrict__ sel_idx,
+                                                          uint32_t* __restrict__ conn, Geom g,
+                                                          int64_t rows)
+{
+    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;    // slice * m + i
+    if (row >= rows) return;
+    const int m = g.n_blocks, n = g.n_select, words = (m + 31) >> 5;
+    const int64_t bh_idx = row / m;
+    const int i = (int)(row - bh_idx * m);
+    uint32_t* base = conn + bh_idx * (int64_t)m * words + (i >> 5);
+    const uint32_t bit = 1u << (i & 31);
+    if (!g.list_only) atomicOr(base + (int64_t)i * words, bit);
+    const int32_t* r = sel_idx + row * n;
+    for (int a = 0; a < n; ++a) {
+        const int j = r[a];
+        if ((unsigned)j < (unsigned)m) atomicOr(base + (int64_t)j * words, bit);
+    }
+}
+
 // plain kernels per (head dim, wavefronts per workgroup); the bodies are templates
 #define BSA_BWD_KERNELS(D, NW)                                                                    \
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dq_d##D##_w##NW(                       \
@@ -716,18 +747,18 @@ __global__ __launch_bounds__(256) void bwd_mfma_prep_kernel(const uint16_t* __re
     }                                                                                             \
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dv_d##D##_w##NW(                       \
         const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
-        const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
+        const float* lse2, const float* delta, const uint32_t* conn, uint16_t* dk,                \
         uint16_t* dv, Geom g, uint32_t n_units)                                                 \
     {                                                                                             \
-        bwdm::dkdv_body<D, NW, bwdm::PASS_DV>(q, k, v, dout, lse2, delta, sel_idx, dk, dv, g,     \
+        bwdm::dkdv_body<D, NW, bwdm::PASS_DV>(q, k, v, dout, lse2, delta, conn, dk, dv, g,        \
                                               n_units);                                        \
     }                                                                                             \
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dk_d##D##_w##NW(                       \
         const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
-        const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
+        const float* lse2, const float* delta, const uint32_t* conn, uint16_t* dk,                \
         uint16_t* dv, Geom g, uint32_t n_units)                                                 \
     {                                                                                             \
-        bwdm::dkdv_body<D, NW, bwdm::PASS_DK>(q, k, v, dout, lse2, delta, sel_idx, dk, dv, g,     \
+        bwdm::dkdv_body<D, NW, bwdm::PASS_DK>(q, k, v, dout, lse2, delta, conn, dk, dv, g,        \
                                               n_units);                                        \
     }
 BSA_BWD_KERNELS(64, 2)
@@ -737,11 +768,11 @@ BSA_BWD_KERNELS(64, 8)
 #define BSA_BWD_FUSED(NW)                                                                         \
     __global__ __launch_bounds__(64 * NW, 2) void bwd_mfma_dkdv_d64_w##NW(                        \
         const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dout,            \
-        const float* lse2, const float* delta, const int32_t* sel_idx, uint16_t* dk,              \
+        const float* lse2, const float* delta, const uint32_t* conn, uint16_t* dk,                \
         uint16_t* dv, Geom g, uint32_t n_units)                                                 \
     {                                                                                             \
         bwdm::dkdv_body<64, NW, bwdm::PASS_DV | bwdm::PASS_DK>(q, k, v, dout, lse2, delta,        \
-                                                               sel_idx, dk, dv, g, n_units);   \
+                                                               conn, dk, dv, g, n_units);      \
     }
 BSA_BWD_FUSED(2)
 BSA_BWD_FUSED(4)
@@ -765,9 +796,18 @@ bool bwd_mfma_supported(bool is_bf16, const Geom& g, int D)
 
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const int32_t* sel_idx, void* dq,
-                           void* dk, void* dv, float* delta, float* lse2, const Geom& g, int D,
-                           int64_t BH, hipStream_t stream)
+                           void* dk, void* dv, float* delta, float* lse2, uint32_t* conn,
+                           const Geom& g, int D, int64_t BH, hipStream_t stream)
 {
+    {
+        const int64_t crows = BH * g.n_blocks, n_words = crows * ((g.n_blocks + 31) >> 5);
+        bwd_connect_clear_kernel<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, stream>>>(
+            conn, n_words);
+        bwd_connect_kernel<<<dim3((unsigned)((crows + 255) / 256)), dim3(256), 0, stream>>>(
+            sel_idx, conn, g, crows);
+        const hipError_t ce = hipGetLastError();
+        if (ce != hipSuccess) return ce;
+    }
     const int64_t rows = BH * g.n_tokens;
     {
         const int64_t threads = rows * (D / 8);
@@ -792,11 +832,11 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
         if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
         bwd_mfma_dv_d##D_##_w##NW_<<<grid_kv, block, 0, stream>>>(                                   \
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
-            lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
+            lse2, delta, conn, (uint16_t*)dk, (uint16_t*)dv, g, sx);                              \
         if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
         bwd_mfma_dk_d##D_##_w##NW_<<<grid_kv, block, 0, stream>>>(                                   \
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
-            lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
+            lse2, delta, conn, (uint16_t*)dk, (uint16_t*)dv, g, sx);                              \
         return hipGetLastError();                                                                 \
     }
 #define BSA_LAUNCH_FUSED(NW_)                                                                     \
@@ -807,7 +847,7 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
         if ((e = hipGetLastError()) != hipSuccess) return e;                                      \
         bwd_mfma_dkdv_d64_w##NW_<<<grid_kv, block, 0, stream>>>(                                     \
             (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout,    \
-            lse2, delta, sel_idx, (uint16_t*)dk, (uint16_t*)dv, g, sx);                           \
+            lse2, delta, conn, (uint16_t*)dk, (uint16_t*)dv, g, sx);                              \
         return hipGetLastError();                                                                 \
     }
     BSA_LAUNCH_FUSED(2)

@@ -63,12 +63,15 @@ hipError_t launch_bwd(bool is_bf16, const void* q, const void* k, const void* v,
                       hipStream_t stream);
 
 // bf16 MFMA backward (head dim 64 or 128, blocks of 64, 128 or 256 tokens);
-// `delta` and `lse2` are fp32 scratch of B*heads*N floats each.
+// `delta` and `lse2` are fp32 scratch of B*heads*N floats each, `conn` scratch of
+// bwd_connection_words(...) 32-bit words (the reverse map of the selection: one
+// bit per (query slice, key block, query block)).
 bool bwd_mfma_supported(bool is_bf16, const Geom& g, int D);
+inline int64_t bwd_connection_words(int m, int64_t BH) { return BH * m * (int64_t)((m + 31) >> 5); }
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const int32_t* sel_idx, void* dq,
-                           void* dk, void* dv, float* delta, float* lse2, const Geom& g, int D,
-                           int64_t BH, hipStream_t stream);
+                           void* dk, void* dv, float* delta, float* lse2, uint32_t* conn,
+                           const Geom& g, int D, int64_t BH, hipStream_t stream);
 
 // Three-branch output: coarse branch (softmax over all pooled key blocks times
 // pooled values, fp32 [B*heads, m, D]), the block lists of the local branch

@@ -48,7 +48,8 @@ def test_workspace_bytes():
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_SELECT) == 3 * per
     assert M.mosaic_bsa_workspace_bytes(p, binding.OP_FWD) == 0
     # delta and lse * log2(e), fp32 [B, heads, N] each
-    assert M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD) == 2 * (1 * 2 * 2048 * 4)
+    # delta + lse in base 2 (fp32 per token) + one bit per (slice, key block, query block)
+    assert M.mosaic_bsa_workspace_bytes(p, binding.OP_BWD) == 2 * (1 * 2 * 2048 * 4) + 2 * 32 * 4
     assert M.mosaic_bsa_workspace_bytes(good(head_dim=48), binding.OP_SELECT) == 0
 
 
