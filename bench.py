@@ -29,11 +29,40 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per forward launch measured with rocprofv3 --pmc (FETCH_SIZE, then
-# WRITE_SIZE, each scaled by the same counter on a plain copy kernel of known
-# size: 2048 and 1024 bytes per count); profiles/fwd_mfma_b64_d64_config3.md.
-# None for workloads that have not been measured.
-MEASURED_FWD_TRAFFIC_BYTES = {3: 17.96e9 + 1.47e9}
+# HBM bytes per forward launch come from the rocprofv3 counter runs summarised
+# under profiles/ (FETCH_SIZE, then WRITE_SIZE, each scaled by the same counter
+# on a plain copy kernel of known size).  A summary carries a line
+#   bench-traffic: config=<id> bytes=<float> sources-sha256=<hex>
+# where the hash covers the sources of the forward kernel it was measured on;
+# the figure is reported only while those sources are unchanged.
+FWD_KERNEL_SOURCES = ("bsa_fwd_mfma.hip", "bsa_mfma_common.h", "bsa_device.h")
+
+
+def fwd_sources_sha256() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in FWD_KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2604_16429_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_fwd_traffic(config_id: int):
+    """(bytes per launch, where it was read) or (None, why not)."""
+    import glob
+    import re
+    sha = fwd_sources_sha256()
+    stale = None
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for m in re.finditer(r"bench-traffic:\s*config=(\d+)\s+bytes=([0-9.eE+]+)\s+"
+                             r"sources-sha256=([0-9a-f]+)", open(path).read()):
+            if int(m.group(1)) != config_id:
+                continue
+            if m.group(3) == sha:
+                return float(m.group(2)), os.path.relpath(path, ROOT)
+            stale = os.path.relpath(path, ROOT)
+    return None, (f"{stale} was measured on other kernel sources" if stale
+                  else "not measured for this workload")
 
 
 def parse_args():
@@ -185,7 +214,7 @@ def main():
     esz = 2 if is_bf16 else 4
     kv_heads = cfg.kv_heads or cfg.heads
     compulsory = 2 * cfg.batch * (cfg.heads + kv_heads) * cfg.n_tokens * cfg.head_dim * esz
-    traffic = MEASURED_FWD_TRAFFIC_BYTES.get(args.config)
+    traffic, traffic_from = measured_fwd_traffic(args.config)
 
     result = {
         "metric": "block-sparse attn tokens/s @1.5deg grid (select + forward); "
@@ -224,7 +253,7 @@ def main():
             "kernel": "attention forward",
             "bound": "mfma", "achieved": eff_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": eff_tflops / MFMA_BF16_PEAK_TFLOPS,
-            "traffic": traffic,
+            "traffic": traffic, "traffic_source": traffic_from,
         },
     }
     if args.hip_graph:
