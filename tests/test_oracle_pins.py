@@ -266,6 +266,32 @@ def test_rows_sum_to_one(oracle):
     np.testing.assert_allclose(P.sum(axis=1), 1.0, rtol=0, atol=1e-14)
 
 
+def test_block_weights_columns_follow_the_gathered_tiles(oracle):
+    """Column c * b + tau of the weights of query block i belongs to in-tile
+    position tau of the c-th attended block (block i itself, then its selected
+    blocks in the order given): pinned against the library softmax over the
+    tiles gathered in exactly that order, and against the output they imply."""
+    import torch
+    c = shape_ns(1, 2, 12, 20, 3, 4, 8, 4)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 1717)
+    idx = random_selection(c, 5)
+    g, i = 1, 7
+    P = oracle.block_weights(s, q, k, v, idx, g, i)
+    b, D = c.block_tokens, c.head_dim
+    qt, kt, vt = (torch.from_numpy(to_tiles(x, c)[0, g].astype(np.float64)) for x in (q, k, v))
+    blocks = [i] + idx[0, g, i].tolist()
+    kk = torch.cat([kt[j] for j in blocks])            # [(n+1) b, D], block-major, tau inside
+    vv = torch.cat([vt[j] for j in blocks])
+    w = torch.softmax(qt[i] @ kk.T / np.sqrt(D), dim=-1).numpy()
+    assert P.shape == (b, len(blocks) * b)
+    np.testing.assert_allclose(P, w, rtol=0, atol=1e-14)
+    out, _ = oracle.fwd(s, q, k, v, idx)
+    np.testing.assert_allclose(P @ vv.numpy(), to_tiles(out, c)[0, g, i], rtol=0, atol=1e-13)
+    # a column order that ignores the selection's order would fail here
+    assert np.abs(P[:, b:2 * b] - w[:, 2 * b:3 * b]).max() > 1e-6
+
+
 def test_unselected_blocks_do_not_matter(oracle):
     c = shape_ns(1, 1, 16, 16, 4, 4, 8, 3)
     s = oracle.shape_of(c)
