@@ -215,6 +215,11 @@ def main():
     kv_heads = cfg.kv_heads or cfg.heads
     compulsory = 2 * cfg.batch * (cfg.heads + kv_heads) * cfg.n_tokens * cfg.head_dim * esz
     traffic, traffic_from = measured_fwd_traffic(args.config)
+    # workgroups per query block in the forward (each gathers the block's tiles once):
+    # head dim 64 groups 4, 2 or 1 sub-blocks of 64 queries, head dim 128 the whole block
+    subs = max(1, cfg.block_tokens // 64)
+    gathers_per_block = (subs // (4 if subs % 4 == 0 else 2 if subs % 2 == 0 else 1)
+                         if cfg.head_dim == 64 else 1)
 
     result = {
         "metric": "block-sparse attn tokens/s @1.5deg grid (select + forward); "
@@ -249,6 +254,17 @@ def main():
         "pct_mfma_peak": 100.0 * eff_tflops / MFMA_BF16_PEAK_TFLOPS,
         "fwd_only_tokens_per_s": tokens / (fwd_ms * 1e-3),
         "compulsory_hbm_gbs": compulsory / (fwd_ms * 1e-3) / 1e9,
+        # K/V bytes that the forward gathers into LDS (every attended tile once per
+        # query block) over the forward time, against what the CUs' vector-memory
+        # path moves at most: 64 B per clock and CU, 256 CUs, 2.4 GHz nominal.  At
+        # 64-token query blocks this path, not the matrix pipe, bounds the kernel.
+        "gather_path": {
+            "achieved_tbs": (cfg.batch * cfg.heads * cfg.n_tokens * (cfg.n_select + 1)
+                             * 2 * cfg.head_dim * esz * gathers_per_block
+                             / (fwd_ms * 1e-3) / 1e12),
+            "peak_tbs": 256 * 64 * 2.4e9 / 1e12,
+            "flop_per_gathered_byte": cfg.block_tokens * 2 / esz / gathers_per_block,
+        },
         "roofline": {
             "kernel": "attention forward",
             "bound": "mfma", "achieved": eff_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
