@@ -257,6 +257,126 @@ void oracle_fwd_blocks(const oracle_shape *s, const float *q, const float *k, co
     }
 }
 
+/* ---- backward on sampled blocks ------------------------------------------
+ * The same closed forms as oracle_bwd, written for one block at a time so that
+ * problems too large for a full pass can be checked on samples.  For sample w =
+ * (slice g, block x):
+ *   dq[w]         rows of dQ of the tokens of block x as a QUERY block;
+ *   dk[w], dv[w]  rows of dK, dV of the tokens of block x as a KEY block: sums
+ *                 over every query block i of the slice that attends to x (i == x
+ *                 or x in sel_idx[i]), query blocks and their tokens ascending.
+ * Each [b, D], in-tile row-major token order.  One key/value head per query
+ * head.  Every query row's weights are recomputed in full (all its (n+1) b
+ * keys): nothing is shared with or taken from another routine's results. */
+static void bwd_row(const oracle_shape *s, const float *q, const float *k, const float *v,
+                    const float *dout, const int32_t *sel_row, int64_t g, int i, int tq,
+                    double scale, double *z /* (n+1) b: P of the row on return */,
+                    double *delta_out)
+{
+    const int D = s->head_dim, n = s->n_select, b = block_tokens(s);
+    const int64_t N = n_tokens(s);
+    const int nk = (n + 1) * b;
+    const int64_t l = token_of(s, i, tq);
+    const float *ql = q + (g * N + l) * D;
+    const float *dol = dout + (g * N + l) * D;
+    double M = -INFINITY;
+    for (int c = 0; c <= n; ++c) {
+        const int beta = (c == 0) ? i : sel_row[c - 1];
+        for (int tau = 0; tau < b; ++tau) {
+            const float *kt = k + (g * N + token_of(s, beta, tau)) * D;
+            double dot = 0.0;
+            for (int d = 0; d < D; ++d) dot += (double)ql[d] * (double)kt[d];
+            z[c * b + tau] = scale * dot;
+            if (z[c * b + tau] > M) M = z[c * b + tau];
+        }
+    }
+    double Z = 0.0;
+    for (int t = 0; t < nk; ++t) { z[t] = exp(z[t] - M); Z += z[t]; }
+    for (int t = 0; t < nk; ++t) z[t] /= Z;
+    double delta = 0.0;                               /* dO_l . O_l, O_l = sum_t P_lt v_t */
+    for (int d = 0; d < D; ++d) {
+        double o = 0.0;
+        for (int c = 0; c <= n; ++c) {
+            const int beta = (c == 0) ? i : sel_row[c - 1];
+            for (int tau = 0; tau < b; ++tau)
+                o += z[c * b + tau] * (double)v[(g * N + token_of(s, beta, tau)) * D + d];
+        }
+        delta += (double)dol[d] * o;
+    }
+    *delta_out = delta;
+}
+
+void oracle_bwd_blocks(const oracle_shape *s, const float *q, const float *k, const float *v,
+                       const float *dout, const int32_t *sel_idx, double scale,
+                       const int64_t *pairs /* [cnt, 2] = (slice, block) */, int64_t cnt,
+                       double *dq, double *dk, double *dv /* [cnt, b, D] each */)
+{
+    const int D = s->head_dim, m = n_blocks(s), n = s->n_select, b = block_tokens(s);
+    const int64_t N = n_tokens(s);
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)s->head_dim);
+    memset(dq, 0, sizeof(double) * (size_t)(cnt * b * D));
+    memset(dk, 0, sizeof(double) * (size_t)(cnt * b * D));
+    memset(dv, 0, sizeof(double) * (size_t)(cnt * b * D));
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)(n + 1) * b);
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t w = 0; w < cnt; ++w) {
+            const int64_t g = pairs[2 * w];
+            const int x = (int)pairs[2 * w + 1];
+            /* dQ of block x as a query block: dQ_l = scale sum_t dS_lt k_t */
+            {
+                const int32_t *sel_row = sel_idx + (g * m + x) * n;
+                for (int tq = 0; tq < b; ++tq) {
+                    double delta;
+                    bwd_row(s, q, k, v, dout, sel_row, g, x, tq, scale, z, &delta);
+                    const float *dol = dout + (g * N + token_of(s, x, tq)) * D;
+                    for (int c = 0; c <= n; ++c) {
+                        const int beta = (c == 0) ? x : sel_row[c - 1];
+                        for (int tau = 0; tau < b; ++tau) {
+                            const int64_t t = token_of(s, beta, tau);
+                            const float *kt = k + (g * N + t) * D;
+                            const float *vt = v + (g * N + t) * D;
+                            double dp = 0.0;
+                            for (int d = 0; d < D; ++d) dp += (double)dol[d] * (double)vt[d];
+                            const double ds = z[c * b + tau] * (dp - delta);
+                            for (int d = 0; d < D; ++d)
+                                dq[(w * b + tq) * D + d] += scale * ds * (double)kt[d];
+                        }
+                    }
+                }
+            }
+            /* dK, dV of block x as a key block */
+            for (int i = 0; i < m; ++i) {
+                const int32_t *sel_row = sel_idx + (g * m + i) * n;
+                int c_of_x = (i == x) ? 0 : -1;
+                for (int r = 0; r < n && c_of_x < 0; ++r)
+                    if (sel_row[r] == x) c_of_x = r + 1;
+                if (c_of_x < 0) continue;
+                for (int tq = 0; tq < b; ++tq) {
+                    double delta;
+                    bwd_row(s, q, k, v, dout, sel_row, g, i, tq, scale, z, &delta);
+                    const int64_t l = token_of(s, i, tq);
+                    const float *ql = q + (g * N + l) * D;
+                    const float *dol = dout + (g * N + l) * D;
+                    for (int tau = 0; tau < b; ++tau) {
+                        const float *vt = v + (g * N + token_of(s, x, tau)) * D;
+                        const double p = z[c_of_x * b + tau];
+                        double dp = 0.0;
+                        for (int d = 0; d < D; ++d) dp += (double)dol[d] * (double)vt[d];
+                        const double ds = p * (dp - delta);
+                        for (int d = 0; d < D; ++d) {
+                            dv[(w * b + tau) * D + d] += p * (double)dol[d];
+                            dk[(w * b + tau) * D + d] += scale * ds * (double)ql[d];
+                        }
+                    }
+                }
+            }
+        }
+        free(z);
+    }
+}
+
 /* Attention weights of one query block: P [b, (n+1)*b] (see attend_block). */
 void oracle_block_weights(const oracle_shape *s, const float *q, const float *k, const float *v,
                           const int32_t *sel_idx, double scale, int64_t g, int i, double *P)

@@ -244,6 +244,34 @@ def bwd(s, q, k, v, dout, sel_idx, scale: float = 0.0):
     return dq, dk, dv
 
 
+def bwd_blocks(s, q, k, v, dout, sel_idx, pairs, scale: float = 0.0):
+    """Gradients on sampled blocks, for problems too large for a full pass:
+    pairs int64 [cnt, 2] = (batch*heads + head, block).  Returns (dq, dk, dv),
+    float64 [cnt, b, D] each, in in-tile token order: dq of the block as a query
+    block, dk and dv of the block as a key block (summed over every query block
+    of the slice that attends to it)."""
+    B, h, N, D, b, m = _dims(s)
+    q, pq = _f32(q)
+    k, pk = _f32(k)
+    v, pv = _f32(v)
+    dout, pd = _f32(dout)
+    _check(s, q, k, v, dout)
+    sel_idx, pi = _i32(sel_idx)
+    pairs = np.ascontiguousarray(pairs, dtype=np.int64).reshape(-1, 2)
+    assert pairs[:, 0].min() >= 0 and pairs[:, 0].max() < B * h
+    assert pairs[:, 1].min() >= 0 and pairs[:, 1].max() < m
+    cnt = pairs.shape[0]
+    dq = np.empty((cnt, b, D), dtype=np.float64)
+    dk = np.empty_like(dq)
+    dv = np.empty_like(dq)
+    _load().oracle_bwd_blocks(ctypes.byref(s), pq, pk, pv, pd, pi, ctypes.c_double(scale),
+                              pairs.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(cnt),
+                              dq.ctypes.data_as(ctypes.c_void_p),
+                              dk.ctypes.data_as(ctypes.c_void_p),
+                              dv.ctypes.data_as(ctypes.c_void_p))
+    return dq, dk, dv
+
+
 # ---------------------------------------------------------------------------
 # Grouped query attention (the paper's Attention paragraph: the queries attend
 # to a smaller number of shared key-value heads).  Reading taken here: query

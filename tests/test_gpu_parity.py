@@ -516,6 +516,63 @@ def test_backward_ensemble_shape_full_grid(G, oracle):
         assert torch.equal(a, b)
 
 
+def sampled_blocks_against_oracle_bwd(G, oracle, p, pairs):
+    """Selection, forward and backward of the whole problem on the GPU (the
+    launch configuration the benchmark times); dQ of the sampled blocks as query
+    blocks and dK, dV of the same blocks as key blocks against the oracle."""
+    import paper_2604_16429_amd as M
+    from paper_2604_16429_amd import binding
+    cfg = p.cfg
+    prm = G.params_of(cfg)
+    q_d, k_d, v_d, do_d = (G.to_dev(x, cfg) for x in (p.q, p.k, p.v, p.dout))
+    idx_d = G.select_dev(cfg, q_d, k_d)
+    out, lse = G.fwd_dev(cfg, q_d, k_d, v_d, idx_d)
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q_d, k_d, v_d))
+    ws = torch.empty(M.mosaic_bsa_workspace_bytes(prm, binding.OP_BWD), dtype=torch.uint8,
+                     device="cuda")
+    M.mosaic_bsa_bwd(prm, q_d, k_d, v_d, out, lse, do_d, idx_d, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    del out, lse, ws
+    s = oracle.shape_of(cfg)
+    ref = oracle.bwd_blocks(s, p.q, p.k, p.v, p.dout, idx_d.cpu().numpy(), pairs)
+    bh = cfg.batch * cfg.heads
+    for w, (g, x) in enumerate(pairs):
+        rows = torch.tensor([oracle.token_of(s, int(x), t) for t in range(cfg.block_tokens)],
+                            device="cuda")
+        got = tuple(t.view(bh, cfg.n_tokens, cfg.head_dim)[int(g)][rows].float().cpu().numpy()
+                    for t in (dq, dk, dv))
+        check_grads(cfg, got, tuple(r[w] for r in ref))
+    for t in (dq, dk, dv):
+        assert bool(torch.isfinite(t.float()).all())        # every row was written
+
+
+def test_backward_quarter_degree_full_size_sampled(G, oracle):
+    """The 0.25 degree configuration at its full size (m = 4050 blocks of 256
+    tokens: eight scan rounds per key block), dO white: gradients of sampled
+    blocks against the oracle."""
+    p = make_problem(4)
+    rng = np.random.default_rng(46)
+    p.dout = round_to_bf16(rng.standard_normal(p.q.shape, dtype=np.float32))
+    cfg = p.cfg
+    pairs = np.array([[int(g), int(x)] for g in rng.choice(cfg.batch * cfg.heads, size=8,
+                                                            replace=False)
+                      for x in rng.choice(cfg.n_blocks, size=2, replace=False)])
+    sampled_blocks_against_oracle_bwd(G, oracle, p, pairs)
+
+
+def test_backward_ensemble_full_size_sampled(G, oracle):
+    """The 1.5 degree ensemble configuration at its full size (batch 24, 16
+    heads), dO white: gradients of sampled blocks against the oracle."""
+    p = make_problem(3)
+    rng = np.random.default_rng(36)
+    p.dout = round_to_bf16(rng.standard_normal(p.q.shape, dtype=np.float32))
+    cfg = p.cfg
+    pairs = np.array([[int(g), int(x)] for g in rng.choice(cfg.batch * cfg.heads, size=16,
+                                                            replace=False)
+                      for x in rng.choice(cfg.n_blocks, size=3, replace=False)])
+    sampled_blocks_against_oracle_bwd(G, oracle, p, pairs)
+
+
 def test_backward_gradient_configuration_fields(G, oracle):
     """Seeded smooth fields of the gradient configuration (tile 8x16, D = 128,
     n = 12, dO white) on a reduced grid, arbitrary selection order; reruns are

@@ -266,6 +266,46 @@ def test_rows_sum_to_one(oracle):
     np.testing.assert_allclose(P.sum(axis=1), 1.0, rtol=0, atol=1e-14)
 
 
+def test_backward_on_sampled_blocks(oracle):
+    """bwd_blocks (gradients of single blocks, for full-size checks) against the
+    library's reverse mode over the gathered-tile attention written with float64
+    tensor operations, and against the full closed-form pass."""
+    import torch
+    c = shape_ns(2, 2, 12, 16, 3, 4, 8, 3)
+    s = oracle.shape_of(c)
+    q, k, v = rand_qkv(c, 2121)
+    dout = rand_qkv(c, 2122)[0]
+    idx = random_selection(c, 9)
+    pairs = np.array([[0, 0], [1, 5], [3, 15], [2, 7], [3, 0]])
+    dq, dk, dv = oracle.bwd_blocks(s, q, k, v, dout, idx, pairs)
+    # library autograd on the definition: per query block, softmax over its gathered tiles
+    tq, tk, tv = (torch.tensor(to_tiles(x, c).astype(np.float64), requires_grad=True)
+                  for x in (q, k, v))
+    td = torch.tensor(to_tiles(dout, c).astype(np.float64))
+    B, h, m, b, D = tq.shape
+    loss = 0.0
+    for e in range(B):
+        for a in range(h):
+            for i in range(m):
+                blocks = [i] + idx[e, a, i].tolist()
+                kk = torch.cat([tk[e, a, j] for j in blocks])
+                vv = torch.cat([tv[e, a, j] for j in blocks])
+                o = torch.softmax(tq[e, a, i] @ kk.T / np.sqrt(D), dim=-1) @ vv
+                loss = loss + (o * td[e, a, i]).sum()
+    loss.backward()
+    for w, (g, x) in enumerate(pairs):
+        e, a = divmod(int(g), h)
+        np.testing.assert_allclose(dq[w], tq.grad[e, a, x].numpy(), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(dk[w], tk.grad[e, a, x].numpy(), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(dv[w], tv.grad[e, a, x].numpy(), rtol=0, atol=1e-12)
+    # and the full pass
+    fq, fk, fv = oracle.bwd(s, q, k, v, dout, idx)
+    for w, (g, x) in enumerate(pairs):
+        e, a = divmod(int(g), h)
+        for got, full in ((dq, fq), (dk, fk), (dv, fv)):
+            np.testing.assert_allclose(got[w], to_tiles(full, c)[e, a, x], rtol=0, atol=1e-13)
+
+
 def test_block_weights_columns_follow_the_gathered_tiles(oracle):
     """Column c * b + tau of the weights of query block i belongs to in-tile
     position tau of the c-th attended block (block i itself, then its selected
