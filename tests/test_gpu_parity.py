@@ -214,6 +214,8 @@ def test_selection_with_more_blocks_than_registers_hold(G, oracle):
     ("bf16", 3, 6, 2, 64, 64, 8, 8, 128, 4),      # 6 key/value slices, head dim 128
     ("bf16", 5, 8, 8, 120, 240, 8, 8, 64, 16),    # 300 pooling blocks per part: the 256 resident
                                                   # pooling workgroups take more than one block
+    ("bf16", 2, 4, 2, 64, 128, 2, 4, 64, 9),      # m = 1024 (64 candidates per lane), grouped heads
+    ("fp32", 3, 2, 1, 48, 100, 2, 2, 32, 70),     # m = 1200, n > 64, odd number of key blocks per thread pair
 ])
 def test_selection_over_parts_of_the_batch(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n):
     """mosaic_bsa_select pools one part of the batch beside the ranking of the
@@ -600,6 +602,7 @@ def test_backward_gradient_configuration_fields(G, oracle):
     ("bf16", 1, 8, 1, 32, 32, 16, 16, 64, 2),    # 256-token blocks, one shared kv head
     ("bf16", 3, 8, 4, 16, 64, 8, 16, 128, 3),    # head dim 128 matrix-core path, 12 kv slices
     ("bf16", 2, 4, 4, 16, 32, 8, 8, 64, 3),      # kv_heads = heads, given explicitly
+    ("bf16", 1, 4, 2, 96, 128, 8, 8, 64, 3),     # m = 192: two scan rounds per key block and head of a group
 ])
 def test_grouped_query_attention(G, oracle, dtype, B, heads, kv_heads, H, W, bh, bw, D, n):
     cfg = shape_ns(B, heads, H, W, bh, bw, D, n, dtype, kv_heads=kv_heads)
