@@ -10,7 +10,7 @@
 // where t runs over the keys of the blocks query block i attends to (itself and
 // its selection) and l over the queries of the blocks that attend to t's block.
 //
-// Two kernels, both built from 32 x 32 x 16 bf16 MFMAs on 64-token tiles that
+// Two main kernels, both built from 32 x 32 x 16 bf16 MFMAs on 64-token tiles that
 // the wavefronts of a workgroup share through LDS (direct-to-LDS gathers,
 // double buffered, one workgroup barrier per tile):
 //   dq kernel    one workgroup per query block, a wavefront per 32 query rows,
@@ -23,8 +23,10 @@
 //                (their K and V rows stay in registers as B operands).  It
 //                lists, in ascending order, the query blocks that attend to
 //                its block (the paper's "query blocks connected to a key/value
-//                block"; no stored reverse map, no floating-point atomics: the
-//                list order fixes the summation order) and walks their Q/dO
+//                block"), from a reverse map of the selection that a small
+//                kernel builds first: a bit matrix, one bit per (key block,
+//                query block).  No floating-point atomics: the ascending list
+//                fixes the summation order.  It then walks their Q/dO
 //                sub-tiles.  Per 32-query tile: S = Q K^T and dP = dO V^T (rows
 //                are queries now: lse and delta come from LDS per row), and
 //                dV^T += dO^T P, dK^T += Q^T dS with the transposing LDS read
