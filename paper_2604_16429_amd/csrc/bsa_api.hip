@@ -379,7 +379,22 @@ namespace {
 // Workspace of the three-branch backward: 256-byte aligned parts in this order.
 struct ThreeBranchBwdLayout {
     size_t attn, do_fg, do_l, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, total;
+    int chunk_rows;        // query blocks per pass of the coarse branch's backward
 };
+
+// The coarse branch's backward keeps the block attention and its gradient of
+// chunk_rows query blocks of every slice at a time: as many as fit this many
+// bytes per matrix, at least 8.
+constexpr size_t kCoarseBwdMatrixBytes = (size_t)64 << 20;
+
+int coarse_bwd_chunk_rows(const Checked& c)
+{
+    const size_t m = (size_t)c.g.n_blocks;
+    size_t rows = kCoarseBwdMatrixBytes / ((size_t)c.BH * m * 4);
+    rows = rows / 8 * 8;
+    if (rows < 8) rows = 8;
+    return (int)(rows < m ? rows : m);
+}
 
 ThreeBranchBwdLayout three_branch_bwd_layout(const Checked& c)
 {
@@ -395,8 +410,9 @@ ThreeBranchBwdLayout three_branch_bwd_layout(const Checked& c)
     w.do_fg = take((size_t)c.BH * N * c.D * esz);
     w.do_l = take((size_t)c.BH * N * c.D * esz);
     w.dobar = take((size_t)c.BH * m * c.D * 4);
-    w.a_mat = take((size_t)c.BH * m * m * 4);
-    w.ds_mat = take((size_t)c.BH * m * m * 4);
+    w.chunk_rows = coarse_bwd_chunk_rows(c);
+    w.a_mat = take((size_t)c.BH * w.chunk_rows * m * 4);
+    w.ds_mat = take((size_t)c.BH * w.chunk_rows * m * 4);
     w.dqbar = take((size_t)c.BH * m * c.D * 4);
     w.dkbar = take((size_t)c.BKV * m * c.D * 4);
     w.dvbar = take((size_t)c.BKV * m * c.D * 4);
@@ -467,7 +483,7 @@ extern "C" int mosaic_bsa_bwd_three_branch(const mosaic_bsa_params* params, int3
                                vbar, dobar, (float*)(ws + w.a_mat),
                                (float*)(ws + w.ds_mat), (float*)(ws + w.dqbar),
                                (float*)(ws + w.dkbar), (float*)(ws + w.dvbar), c.g, c.D, c.BH,
-                               stream) != hipSuccess)
+                               w.chunk_rows, stream) != hipSuccess)
         return MOSAIC_BSA_ERR_LAUNCH;
     // local branch, added in place together with the block's pooled gradient / b:
     // dx = selection branch + local branch + coarse branch

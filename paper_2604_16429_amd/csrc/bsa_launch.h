@@ -90,7 +90,8 @@ hipError_t launch_combine(bool is_bf16, const float* obar, const void* o_fg, con
 
 // Backward of the three-branch output: upstream gradients of the two attention
 // branches and the gate gradients; the coarse branch's gradients on the pooled
-// tensors (a_mat, ds_mat: fp32 scratch [B*heads, m, m]).
+// tensors, chunk_rows query blocks at a time (a_mat, ds_mat: fp32 scratch
+// [B*heads, chunk_rows, m]).
 int coarse_bwd_group_size(int m, int D);
 hipError_t launch_branch_grads(bool is_bf16, const float* obar, const void* o_fg, const void* o_l,
                                const float* gates, const void* dout, void* do_fg, void* do_l,
@@ -99,7 +100,7 @@ hipError_t launch_branch_grads(bool is_bf16, const float* obar, const void* o_fg
 hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* kbar_il,
                              const float* vbar, const float* dobar, float* a_mat, float* ds_mat, float* dqbar,
                              float* dkbar, float* dvbar, const Geom& g, int D, int64_t BH,
-                             hipStream_t stream);
+                             int chunk_rows, hipStream_t stream);
 
 // Measurement aid: `workgroups` x 4 wavefronts, each issuing 16 * iters
 // v_mfma_f32_32x32x16_bf16 on register operands; sink: workgroups * 256 floats.

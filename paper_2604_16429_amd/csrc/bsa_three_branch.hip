@@ -308,12 +308,17 @@ hipError_t launch_combine(bool is_bf16, const float* obar, const void* o_fg, con
 //                        of the block of g_cg(l) * dO_l, fp32 [B*h, m, D].
 //   coarse_bwd_rows_kernel  per query block: block attention a_i, da_ij =
 //                        dobar_i . vbar_j, ds_ij = a_ij (da_ij - sum_j a_ij
-//                        da_ij); writes a and ds (fp32 [B*h, m, m]) and
-//                        dqbar_i = scale * sum_j ds_ij kbar_j.
+//                        da_ij); writes a and ds and dqbar_i = scale * sum_j
+//                        ds_ij kbar_j.
 //   coarse_bwd_cols_kernel  per key block and key/value slice: dvbar_j =
 //                        sum_i a_ij dobar_i and dkbar_j = scale * sum_i ds_ij
-//                        qbar_i, summed over the query heads of the group in
-//                        ascending order.
+//                        qbar_i.
+// The two kernels alternate over chunks of R query blocks, so that a and ds
+// are fp32 [B*h, R, m] with R chosen by the caller's scratch size, not
+// [B*h, m, m]: the column kernel carries its sums from chunk to chunk in
+// dkbar / dvbar (unscaled until the last chunk).  Summation order: chunks
+// ascending, inside a chunk the query heads of the group ascending, inside a
+// head the query blocks ascending.
 // The pooled gradients reach the tokens in the local branch's attention
 // backward, whose stores add (pooled gradient of the token's block) / b: the
 // mean pooling hands every token of a block the same share.
@@ -407,8 +412,10 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
     const float* __restrict__ qbar, const float* __restrict__ kbar,
     const float* __restrict__ kbar_il, const float* __restrict__ vbar,
     const float* __restrict__ dobar, float* __restrict__ a_out, float* __restrict__ ds_out,
-    float* __restrict__ dqbar, Geom g, int G)
+    float* __restrict__ dqbar, Geom g, int G, int R, int r0, int r1)
 {
+    // query blocks r0 .. r1-1 of every slice; a_out, ds_out: [B*h, R, m] with
+    // R >= r1 - r0
     constexpr int CG = D / 4, JP = 256 / CG;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int m = g.n_blocks;
@@ -416,14 +423,15 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
     float* sc_s = red_s + 4 * G * D;                 // [G][m]: scores -> weights a
     float* da_s = sc_s + G * m;                      // [G][m]: da -> ds
 
-    const int groups = (m + G - 1) / G;
+    const int groups = (r1 - r0 + G - 1) / G;
     const int64_t bh_idx = blockIdx.x / groups;
-    const int i0 = (int)(blockIdx.x - bh_idx * groups) * G;
-    const int rows = min(G, m - i0);
+    const int i0 = r0 + (int)(blockIdx.x - bh_idx * groups) * G;
+    const int rows = min(G, r1 - i0);
     const int64_t kv = kv_slice_of(g, bh_idx);
     kbar += kv * m * D;
     vbar += kv * m * D;
     const int64_t row0 = bh_idx * m + i0;
+    const int64_t out_row0 = bh_idx * R + (i0 - r0);    // row of a_out / ds_out
     if (kbar_il) kbar_il += kv * m * D;              // per slice [D/4][m][4]
 
     // scores (base-2 domain) and da_ij = dobar_i . vbar_j; the rows of qbar and
@@ -483,8 +491,8 @@ __global__ __launch_bounds__(256) void coarse_bwd_rows_kernel(
         }
         dot = wave_sum(dot);
         // ds_ij, and both matrices to global memory for the column pass
-        float* a_row = a_out + (row0 + r) * (int64_t)m;
-        float* ds_row = ds_out + (row0 + r) * (int64_t)m;
+        float* a_row = a_out + (out_row0 + r) * (int64_t)m;
+        float* ds_row = ds_out + (out_row0 + r) * (int64_t)m;
         for (int j = lane; j < m; j += 64) {
             const float a = row[j];
             const float ds = a * (da_s[r * m + j] - dot);
@@ -549,15 +557,18 @@ int coarse_bwd_group_size(int m, int D)
 }
 
 // One lane per key block j (a wavefront covers 64 consecutive ones of one
-// key/value slice): it walks the query blocks i in ascending order, reading
-// column j of a and ds (lanes read consecutive addresses) and adding
-// a_ij * dobar_i and ds_ij * qbar_i into its D-channel accumulators; the rows
-// dobar_i and qbar_i are the same for the whole wavefront.
+// key/value slice): it walks the query blocks i = r0 .. r1-1 in ascending
+// order, reading column j of a and ds ([B*h, R, m]: lanes read consecutive
+// addresses) and adding a_ij * dobar_i and ds_ij * qbar_i into its D-channel
+// accumulators; the rows dobar_i and qbar_i are the same for the whole
+// wavefront.  The sums start from what dkbar / dvbar hold unless r0 == 0 and
+// are scaled only when r1 == m, so a sequence of calls over ascending chunks
+// adds every term once, in a fixed order.
 template <int D>
 __global__ __launch_bounds__(256) void coarse_bwd_cols_kernel(
     const float* __restrict__ qbar, const float* __restrict__ dobar,
     const float* __restrict__ a_in, const float* __restrict__ ds_in, float* __restrict__ dkbar,
-    float* __restrict__ dvbar, Geom g, int64_t waves)
+    float* __restrict__ dvbar, Geom g, int64_t waves, int R, int r0, int r1)
 {
     const int m = g.n_blocks;
     const int chunks = (m + 63) / 64;
@@ -572,17 +583,28 @@ __global__ __launch_bounds__(256) void coarse_bwd_cols_kernel(
     const int64_t bh_first = (kv / kv_heads) * g.heads + (kv % kv_heads) * g.kv_group;
 
     float acc_k[D], acc_v[D];
+    float* dk_row = dkbar + (kv * m + jc) * D;
+    float* dv_row = dvbar + (kv * m + jc) * D;
+    if (r0 == 0) {
 #pragma unroll
-    for (int d = 0; d < D; ++d) { acc_k[d] = 0.0f; acc_v[d] = 0.0f; }
+        for (int d = 0; d < D; ++d) { acc_k[d] = 0.0f; acc_v[d] = 0.0f; }
+    } else {
+#pragma unroll
+        for (int d = 0; d < D; d += 4) {
+            const float4 pk = *(const float4*)(dk_row + d), pv = *(const float4*)(dv_row + d);
+            acc_k[d] = pk.x; acc_k[d + 1] = pk.y; acc_k[d + 2] = pk.z; acc_k[d + 3] = pk.w;
+            acc_v[d] = pv.x; acc_v[d + 1] = pv.y; acc_v[d + 2] = pv.z; acc_v[d + 3] = pv.w;
+        }
+    }
     // query heads of the group in ascending order, query blocks ascending
     for (int gq = 0; gq < g.kv_group; ++gq) {
         const int64_t bh = bh_first + gq;
-        const float* a_col = a_in + bh * m * (int64_t)m + jc;
-        const float* s_col = ds_in + bh * m * (int64_t)m + jc;
+        const float* a_col = a_in + bh * R * (int64_t)m + jc;
+        const float* s_col = ds_in + bh * R * (int64_t)m + jc;
         const float* q_rows = qbar + bh * m * D;
         const float* d_rows = dobar + bh * m * D;
-        for (int i = 0; i < m; ++i) {
-            const float a = a_col[(int64_t)i * m], ds = s_col[(int64_t)i * m];
+        for (int i = r0; i < r1; ++i) {
+            const float a = a_col[(int64_t)(i - r0) * m], ds = s_col[(int64_t)(i - r0) * m];
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 acc_v[d] = fmaf(a, d_rows[i * D + d], acc_v[d]);
@@ -591,12 +613,11 @@ __global__ __launch_bounds__(256) void coarse_bwd_cols_kernel(
         }
     }
     if (j < m) {
-        float* dk_row = dkbar + (kv * m + j) * D;
-        float* dv_row = dvbar + (kv * m + j) * D;
+        const float fk = r1 == m ? g.scale : 1.0f;
 #pragma unroll
         for (int d = 0; d < D; d += 4) {
-            *(float4*)(dk_row + d) = make_float4(acc_k[d] * g.scale, acc_k[d + 1] * g.scale,
-                                                 acc_k[d + 2] * g.scale, acc_k[d + 3] * g.scale);
+            *(float4*)(dk_row + d) = make_float4(acc_k[d] * fk, acc_k[d + 1] * fk,
+                                                 acc_k[d + 2] * fk, acc_k[d + 3] * fk);
             *(float4*)(dv_row + d) =
                 make_float4(acc_v[d], acc_v[d + 1], acc_v[d + 2], acc_v[d + 3]);
         }
@@ -634,7 +655,7 @@ template <int D>
 static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, const float* kbar_il,
                                       const float* vbar, const float* dobar, float* a_mat, float* ds_mat,
                                       float* dqbar, float* dkbar, float* dvbar, const Geom& g,
-                                      int64_t BH, hipStream_t stream)
+                                      int64_t BH, int chunk_rows, hipStream_t stream)
 {
     const int G = coarse_bwd_group_size(g.n_blocks, D);
     if (G == 0) return hipErrorInvalidValue;
@@ -649,27 +670,36 @@ static hipError_t launch_coarse_bwd_t(const float* qbar, const float* kbar, cons
         attr_set[dev] = true;
     }
     const int m = g.n_blocks;
-    hipLaunchKernelGGL((coarse_bwd_rows_kernel<D>), dim3((unsigned)(BH * ((m + G - 1) / G))),
-                       dim3(256), coarse_bwd_lds_bytes(G, m, D), stream, qbar, kbar, kbar_il, vbar,
-                       dobar, a_mat, ds_mat, dqbar, g, G);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const int R = chunk_rows;
+    if (R < 1) return hipErrorInvalidValue;
     const int64_t BKV = BH / g.kv_group;
     const int64_t waves = BKV * ((m + 63) / 64);
-    hipLaunchKernelGGL((coarse_bwd_cols_kernel<D>), dim3((unsigned)((waves + 3) / 4)), dim3(256),
-                       0, stream, qbar, dobar, a_mat, ds_mat, dkbar, dvbar, g, waves);
-    return hipGetLastError();
+    for (int r0 = 0; r0 < m; r0 += R) {
+        const int r1 = r0 + R < m ? r0 + R : m;
+        hipLaunchKernelGGL((coarse_bwd_rows_kernel<D>),
+                           dim3((unsigned)(BH * ((r1 - r0 + G - 1) / G))), dim3(256),
+                           coarse_bwd_lds_bytes(G, m, D), stream, qbar, kbar, kbar_il, vbar, dobar,
+                           a_mat, ds_mat, dqbar, g, G, R, r0, r1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((coarse_bwd_cols_kernel<D>), dim3((unsigned)((waves + 3) / 4)),
+                           dim3(256), 0, stream, qbar, dobar, a_mat, ds_mat, dkbar, dvbar, g,
+                           waves, R, r0, r1);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_coarse_bwd(const float* qbar, const float* kbar, const float* kbar_il,
                              const float* vbar, const float* dobar, float* a_mat, float* ds_mat, float* dqbar,
                              float* dkbar, float* dvbar, const Geom& g, int D, int64_t BH,
-                             hipStream_t stream)
+                             int chunk_rows, hipStream_t stream)
 {
     switch (D) {
-    case 32: return launch_coarse_bwd_t<32>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
-    case 64: return launch_coarse_bwd_t<64>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
-    case 128: return launch_coarse_bwd_t<128>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, stream);
+    case 32: return launch_coarse_bwd_t<32>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, chunk_rows, stream);
+    case 64: return launch_coarse_bwd_t<64>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, chunk_rows, stream);
+    case 128: return launch_coarse_bwd_t<128>(qbar, kbar, kbar_il, vbar, dobar, a_mat, ds_mat, dqbar, dkbar, dvbar, g, BH, chunk_rows, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -720,6 +720,38 @@ def test_three_branch_backward(G, oracle, dtype, B, heads, kv_heads, H, W, bh, b
     assert np.abs(dg - rg).max() <= tol
 
 
+@pytest.mark.parametrize("kv_heads", [0, 4])
+def test_three_branch_backward_coarse_branch_in_row_chunks(G, oracle, kv_heads):
+    """With this many slices and blocks the block attention of the coarse branch
+    and its gradient (B*h*m*m values each) exceed what the backward keeps of
+    them, so it walks the query blocks in chunks and carries the column sums
+    from chunk to chunk.  Batch entries and key/value heads are independent:
+    sampled groups of the big problem against the oracle run on that group alone."""
+    B, heads, H, W, D, n = 12, 8, 120, 240, 64, 4
+    hk = kv_heads or heads
+    group = heads // hk
+    cfg = shape_ns(B, heads, H, W, 8, 8, D, n, "bf16", kv_heads=kv_heads)
+    assert B * heads * cfg.n_blocks ** 2 * 4 > 64 << 20       # more than one chunk
+    rng = np.random.default_rng(9100 + hk)
+    q, dout = (round_to_bf16(rng.standard_normal((B, heads, H * W, D), dtype=np.float32))
+               for _ in range(2))
+    k, v = (round_to_bf16(rng.standard_normal((B, hk, H * W, D), dtype=np.float32))
+            for _ in range(2))
+    gates = rng.uniform(0.0, 1.0, size=(B, heads, H * W, 3)).astype(np.float32)
+    out, sel, dq, dk, dv, dg = G.gpu_three_branch_fwd_bwd(cfg, q, k, v, gates, dout, 3, 3)
+    one = shape_ns(1, group, H, W, 8, 8, D, n, "bf16", kv_heads=1 if kv_heads else 0)
+    s = oracle.shape_of(one, own_is_candidate=True)
+    for e, a in ((0, 0), (7, hk - 1), (11, hk // 2)):          # (batch entry, key/value head)
+        qs = slice(a * group, (a + 1) * group)
+        sub = lambda x, hs: np.ascontiguousarray(x[e:e + 1, hs])
+        ks = slice(a, a + 1)
+        rq, rk, rv, rg, _ = oracle.bwd_three_branch(s, sub(q, qs), sub(k, ks), sub(v, ks),
+                                                    sub(gates, qs), sub(dout, qs), sub(sel, qs),
+                                                    3, 3)
+        check_grads(one, (sub(dq, qs), sub(dk, ks), sub(dv, ks)), (rq, rk, rv))
+        assert np.abs(sub(dg, qs) - rg).max() <= 2e-2 * max(1.0, np.abs(rg).max())
+
+
 def test_select_and_forward_replay_from_a_hip_graph(G, oracle):
     """The entry points allocate nothing and launch on the caller's stream, so a
     select + forward step can be captured once and replayed (the small
