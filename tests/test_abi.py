@@ -111,6 +111,25 @@ def test_null_alignment_and_workspace_errors():
     assert e.value.code == -7
 
 
+def test_more_blocks_than_the_ranking_holds_are_rejected_on_the_host():
+    """The scores of one query block must fit a workgroup's LDS (36,864 words):
+    m = 36,864 is accepted (a missing workspace is what is reported), the next
+    larger grid of 1 x 1 tiles is a shape error, before anything is launched."""
+    fake = 0x1000
+    ok = good(heads=1, grid_h=192, grid_w=192, block_h=1, block_w=1, n_select=3)
+    assert M.mosaic_bsa_workspace_bytes(ok, binding.OP_SELECT) > 0
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_select(ok, fake, fake, fake, fake, stream=0, workspace_bytes=0)
+    assert e.value.code == -6
+    big = good(heads=1, grid_h=193, grid_w=192, block_h=1, block_w=1, n_select=3)
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_select(big, fake, fake, fake, fake, stream=0, workspace_bytes=1 << 40)
+    assert e.value.code == -2
+    with pytest.raises(M.BsaError) as e:
+        M.mosaic_bsa_select_static(big, fake, fake, fake, stream=0)
+    assert e.value.code == -2
+
+
 def test_strerror_covers_all_codes():
     texts = {M.mosaic_bsa_strerror(c) for c in range(0, -10, -1)}
     assert len(texts) == 10 and "unknown error code" not in texts

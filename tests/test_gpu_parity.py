@@ -207,6 +207,17 @@ def test_selection_with_more_blocks_than_registers_hold(G, oracle):
     assert np.array_equal(G.gpu_select(cfg, qq, kq), oracle.select(s, qq, kq))
 
 
+def test_selection_at_the_largest_number_of_blocks(G, oracle):
+    """m = 36,864: the most blocks whose scores of ONE query block fit the
+    workgroup's LDS (one query block per workgroup); every row against the
+    oracle.  (The next larger grid is rejected on the host: test_abi.)"""
+    cfg = shape_ns(1, 1, 192, 192, 1, 1, 32, 3, "fp32")
+    assert cfg.n_blocks == 36864
+    s = oracle.shape_of(cfg)
+    q, k, _ = rand_qkv(cfg, 960)
+    assert np.array_equal(G.gpu_select(cfg, q, k), oracle.select(s, q, k))
+
+
 @pytest.mark.parametrize("dtype,B,heads,kv_heads,H,W,bh,bw,D,n", [
     ("fp32", 1, 1, 1, 32, 64, 8, 8, 32, 5),       # one slice: a single part
     ("fp32", 1, 3, 3, 32, 64, 8, 8, 32, 5),       # three slices: three parts
