@@ -48,7 +48,10 @@
 // after with the same half of the next tile, which then has three steps (3/4
 // of a pair) to arrive.  The 8 loads of a refill are spread over the 8 MFMA
 // slots of a step: a burst would hold the wavefront at the CU's shared address
-// unit.
+// unit.  Workgroups of 2 or 4 wavefronts (blocks of 128 or 256 tokens, whose
+// sub-blocks share the tiles) have the LDS for two tiles: consecutive pairs
+// alternate between two sets of buffers and a half is refilled with the tile
+// after the next, which has seven steps to arrive.
 //
 // Softmax without a row maximum per tile.  m_ref is the reference the
 // exponentials are taken against.  A tile first computes its weights against
@@ -73,21 +76,27 @@ __device__ __forceinline__ int swz(int row, int chunk)
     return chunk ^ (((row & 3) << 1) | ((row >> 2) & 1));
 }
 
-// Gather one 32-token x 64-channel bf16 half tile into LDS (4 KiB, rows
-// swizzled) with buffer loads that write LDS directly.  A whole 64-token tile
-// takes 8 such instructions; instruction r brings tile rows 8r..8r+7 and lane
-// l fills LDS chunk l of that 1 KiB slab, i.e. row 8r + l/8, swizzled chunk
-// l%8.  The per-lane byte offsets inside a block (voff) are fixed for the whole
-// kernel and the block origin is wave-uniform (soffset), so a gather costs no
-// vector ALU work.  The buffer descriptor bounds the slice: an out-of-range
-// block index reads zeros instead of faulting, and a descriptor of zero
-// records makes the load a no-op.
-template <int R>
+// Gather of a 64-token x 64-channel bf16 tile into LDS (two 4 KiB halves, rows
+// swizzled) with buffer loads that write LDS directly.  A tile takes 8 such
+// instructions; instruction r ("slab" r) brings tile rows 8r..8r+7 and lane l
+// fills LDS chunk l of that 1 KiB slab, i.e. row 8r + l/8, swizzled chunk l%8.
+// The wavefronts of a workgroup split the slabs: wavefront w issues slabs
+// NW j + w, j = 0 .. 8/NW - 1, the first half of them into the lower half tile.
+// The per-lane byte offsets of a wavefront's slabs inside a block (voff[j]) are
+// fixed for the whole kernel, the block origin is wave-uniform (soffset) and so
+// is the LDS address (half tile + ((NW j + w) % 4) KiB), so a gather costs no
+// vector ALU work and no branch.  The buffer descriptor bounds the slice: an
+// out-of-range block index reads zeros instead of faulting, and a descriptor
+// of zero records makes the load a no-op.
+template <int NW, int J>
 __device__ __forceinline__ void gather_slab(__amdgpu_buffer_rsrc_t rsrc, uint32_t origin_bytes,
-                                            const uint32_t (&voff)[8], unsigned char* lds_half)
+                                            const uint32_t (&voff)[8 / NW], unsigned char* lds_half,
+                                            uint32_t wave_kib)
 {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds_half + (R & 3) * 1024), 16,
-                                             voff[R], origin_bytes, 0, 0);
+    // J-th slab of this wavefront: slab NW * J + wave of the tile
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        rsrc, LDS_PTR(void, lds_half + ((NW * J) & 3) * 1024 + wave_kib), 16, voff[J],
+        origin_bytes, 0, 0);
 }
 
 // The two half tiles that a step refills, spread over its 8 MFMA slots: a
@@ -104,8 +113,8 @@ struct Refill {
 // the S tile J+1 and the 4 MFMAs that add tile J-1 to O, and behind each the
 // vector work of one eighth of the weights of tile J, skewed by one slot
 // (fma for slot k+1, exp2 for slot k, rounding pack + row sum for slot k-1) so
-// that no instruction waits for the one before it.  With REFILL, slot r also
-// issues slab r of a K/V refill.  S tiles and P tiles are indexed by query
+// that no instruction waits for the one before it.  With REFILL, every NW-th
+// slot also issues one of this wavefront's slabs of a K/V refill.  S tiles and P tiles are indexed by query
 // half: the tile being weighted and its neighbours in the pipeline always
 // differ in it.  Returns this lane's sum of the tile's fp32 weights.
 template <int J, bool REFILL, int NW, class Mid>
@@ -113,8 +122,8 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
                                                f32x16 (&oacc)[2][2], const bf16x8 (&qf)[2][4],
                                                const bf16x8 (&kf)[2][4],
                                                const bf16x8 (&vf)[2][4], float c2, float neg_m,
-                                               const Refill& rf, const uint32_t (&voff)[8],
-                                               int wave, Mid mid)
+                                               const Refill& rf, const uint32_t (&voff)[8 / NW],
+                                               uint32_t wave_kib, Mid mid)
 {
     constexpr int nt = J & 1;
     constexpr int mt_n = ((J + 1) & 3) >> 1, nt_n = (J + 1) & 1;   // next tile: S
@@ -144,17 +153,19 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
             oacc[dt][nt_p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 vf[dt][2 * mt_p + h], p[nt_p][h], oacc[dt][nt_p], 0, 0, 0);
         }
-        if (REFILL && (NW == 1 || (k & (NW - 1)) == wave)) {
-            // (the wavefronts of a workgroup share the refill: slot k belongs
-            // to wavefront k mod NW)
+        if (REFILL && k % NW == 0) {
+            // (the wavefronts of a workgroup share the refill: every NW-th slot
+            // issues this wavefront's next slab, slab k + wave of the tile)
             if (k < 4)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rf.rsrc_a, (__attribute__((address_space(3))) void*)(rf.lds_a + k * 1024), 16,
-                    voff[k], rf.origin_a, 0, 0);
+                    rf.rsrc_a,
+                    (__attribute__((address_space(3))) void*)(rf.lds_a + k * 1024 + wave_kib), 16,
+                    voff[k / NW], rf.origin_a, 0, 0);
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rf.rsrc_b, (__attribute__((address_space(3))) void*)(rf.lds_b + (k - 4) * 1024),
-                    16, voff[k], rf.origin_b, 0, 0);
+                    rf.rsrc_b,
+                    (__attribute__((address_space(3))) void*)(rf.lds_b + (k - 4) * 1024 + wave_kib),
+                    16, voff[k / NW], rf.origin_b, 0, 0);
         }
         // exp2 of this slot's pair, fma of the next slot's, pack and row sums
         // of the previous slot's: nothing waits for the instruction before it.
@@ -199,13 +210,16 @@ __device__ __forceinline__ float pipeline_step(f32x16 (&s)[2], bf16x8 (&p)[2][2]
     return rs0 + rs1;
 }
 
+// compile-time index of an LDS set
+template <int S> struct SetTag { static constexpr int value = S; };
+
 // The kernel body for workgroups of NW wavefronts.  NW consecutive 64-query
 // sub-blocks of one query block attend to the same K/V tiles, so with NW > 1
 // the tiles in LDS are shared: the loads of a refill are split between the
 // wavefronts and each group of half tiles takes two workgroup barriers per
 // pair, "all reads done" before its refill is issued and "all loads landed"
 // (each wavefront waits for its own loads first) before it is read again.
-template <int NW>
+template <int NW, int DEPTH>
 __device__ __forceinline__ void fwd_mfma_d64_body(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,
@@ -215,18 +229,39 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     constexpr int D = 64;
     static_assert(NW == 1 || NW == 2 || NW == 4, "8 loads per refill step, split between waves");
     auto wg_barrier = [] { if (NW > 1) __builtin_amdgcn_s_barrier(); };
-    // all but this wavefront's loads of the most recent refill step (8 / NW)
+    static_assert(DEPTH == 1 || (DEPTH == 2 && NW > 1), "one K/V tile in LDS, or two (even pair counts only)");
+    // every load older than this wavefront's share (8 / NW each) of the most
+    // recent 2 * DEPTH - 1 refill steps has landed
     auto wait_older_loads = [] {
-        if (NW == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        if (NW == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        if (NW == 4) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        if (NW == 1 && DEPTH == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (NW == 2 && DEPTH == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (NW == 4 && DEPTH == 1) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        if (NW == 1 && DEPTH == 2) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        if (NW == 2 && DEPTH == 2) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        if (NW == 4 && DEPTH == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
     };
-    // K and V tiles as two 32-key halves each; separate objects, so that reads
-    // of one half are not ordered behind gathers into another
-    __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[32 * 128];
-    __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[32 * 128];
-    __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[32 * 128];
-    __shared__ __attribute__((aligned(1024))) unsigned char v_lds1[32 * 128];
+    // K and V tiles as two 32-key halves each, DEPTH sets of them (pair c lives
+    // in set c % DEPTH).  Halves that are read at the same point of the
+    // pipeline and refilled in the same step share an object; reads of one
+    // object are not ordered behind gathers into another (the compiler tracks
+    // a limited number of them, beyond which it waits for every load):
+    //   x_*: V half 0 and K half 1 of a set (read in step 3 of the pair before,
+    //        refilled in step 0);
+    //   y_*: V half 1 of a set and K half 0 of the other set (DEPTH 1: of the
+    //        same set), read in step 1 and refilled in step 2.
+    __shared__ __attribute__((aligned(1024))) unsigned char x_a[2][32 * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char y_a[2][32 * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char x_b[DEPTH == 2 ? 2 : 1][DEPTH == 2 ? 32 * 128 : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char y_b[DEPTH == 2 ? 2 : 1][DEPTH == 2 ? 32 * 128 : 16];
+    unsigned char* const v_lds0_a = x_a[0];
+    unsigned char* const k_lds1_a = x_a[1];
+    unsigned char* const v_lds0_b = x_b[0];
+    unsigned char* const k_lds1_b = x_b[DEPTH - 1];
+    // y_a: V half 1 of set a with K half 0 of set b (DEPTH 1: of set a)
+    unsigned char* const v_lds1_a = y_a[0];
+    unsigned char* const k_lds0_b = y_a[1];
+    unsigned char* const v_lds1_b = y_b[0];
+    unsigned char* const k_lds0_a = DEPTH == 2 ? y_b[DEPTH - 1] : y_a[1];
     __shared__ int order_s[NW][64];
 
     const int lane = threadIdx.x & 63;
@@ -282,41 +317,43 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     // the tile width is a power of two
     const int bw_shift = __builtin_ctz((unsigned)g.block_w);
     // byte offset (inside a 64-token sub-tile) of the 16-byte chunk this lane
-    // gathers in slab r: sub-tile row 8r + lane/8, global chunk = swizzle of its LDS slot
-    uint32_t voff[8];
+    // gathers in its wavefront's j-th slab (slab r = NW j + wave): sub-tile row
+    // 8r + lane/8, global chunk = swizzle of its LDS slot
+    uint32_t voff[8 / NW];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int t = 8 * r + (lane >> 3);
-        voff[r] = (uint32_t)((sub_tile_pos(g, t) * D + swz(t, lane & 7) * 8) * 2);
+    for (int j = 0; j < 8 / NW; ++j) {
+        const int t = 8 * (NW * j + wave) + (lane >> 3);
+        voff[j] = (uint32_t)((sub_tile_pos(g, t) * D + swz(t, lane & 7) * 8) * 2);
     }
+    const uint32_t wave_kib = (uint32_t)wave * 1024u;   // this wavefront's slab inside a group of NW
     auto origin_of = [&](int beta) -> uint32_t {     // byte offset of a block's first token
         const int br = beta / g.blocks_per_row, bc = beta - br * g.blocks_per_row;
         return (uint32_t)((br * g.block_h * g.grid_w + bc * g.block_w) * (D * 2));
     };
 
-    // K(0) and V(0) go to LDS
+    // this wavefront's slabs of a lower / upper half tile
+#define BSA_GATHER_HALF_LO(RSRC, ORIGIN, LDS)                                          \
+    gather_slab<NW, 0>(RSRC, ORIGIN, voff, LDS, wave_kib);                             \
+    if (NW <= 2) gather_slab<NW, NW <= 2 ? 1 : 0>(RSRC, ORIGIN, voff, LDS, wave_kib);   \
+    if (NW == 1) {                                                                     \
+        gather_slab<NW, NW == 1 ? 2 : 0>(RSRC, ORIGIN, voff, LDS, wave_kib);           \
+        gather_slab<NW, NW == 1 ? 3 : 0>(RSRC, ORIGIN, voff, LDS, wave_kib);           \
+    }
+#define BSA_GATHER_HALF_HI(RSRC, ORIGIN, LDS)                                          \
+    gather_slab<NW, 4 / NW>(RSRC, ORIGIN, voff, LDS, wave_kib);                        \
+    if (NW <= 2) gather_slab<NW, NW <= 2 ? 4 / NW + 1 : 0>(RSRC, ORIGIN, voff, LDS, wave_kib); \
+    if (NW == 1) {                                                                     \
+        gather_slab<NW, NW == 1 ? 6 : 0>(RSRC, ORIGIN, voff, LDS, wave_kib);           \
+        gather_slab<NW, NW == 1 ? 7 : 0>(RSRC, ORIGIN, voff, LDS, wave_kib);           \
+    }
+    // K(0) and V(0) go to LDS (set a), in the order K half 0, K half 1, V half 0,
+    // V half 1: the waits below count on it
     {
         const uint32_t origin_0 = origin_of(first) + (uint32_t)0;
-        // (split between the wavefronts of the workgroup: slab r belongs to
-        // wavefront r mod NW)
-#define BSA_GATHER_MINE(R, RSRC, ORIGIN, LDS) \
-    if (NW == 1 || ((R) & (NW - 1)) == wave) gather_slab<R>(RSRC, ORIGIN, voff, LDS)
-        BSA_GATHER_MINE(0, k_rsrc, origin_0, k_lds0);
-        BSA_GATHER_MINE(1, k_rsrc, origin_0, k_lds0);
-        BSA_GATHER_MINE(2, k_rsrc, origin_0, k_lds0);
-        BSA_GATHER_MINE(3, k_rsrc, origin_0, k_lds0);
-        BSA_GATHER_MINE(4, k_rsrc, origin_0, k_lds1);
-        BSA_GATHER_MINE(5, k_rsrc, origin_0, k_lds1);
-        BSA_GATHER_MINE(6, k_rsrc, origin_0, k_lds1);
-        BSA_GATHER_MINE(7, k_rsrc, origin_0, k_lds1);
-        BSA_GATHER_MINE(0, v_rsrc, origin_0, v_lds0);
-        BSA_GATHER_MINE(1, v_rsrc, origin_0, v_lds0);
-        BSA_GATHER_MINE(2, v_rsrc, origin_0, v_lds0);
-        BSA_GATHER_MINE(3, v_rsrc, origin_0, v_lds0);
-        BSA_GATHER_MINE(4, v_rsrc, origin_0, v_lds1);
-        BSA_GATHER_MINE(5, v_rsrc, origin_0, v_lds1);
-        BSA_GATHER_MINE(6, v_rsrc, origin_0, v_lds1);
-        BSA_GATHER_MINE(7, v_rsrc, origin_0, v_lds1);
+        BSA_GATHER_HALF_LO(k_rsrc, origin_0, k_lds0_a);
+        BSA_GATHER_HALF_HI(k_rsrc, origin_0, k_lds1_a);
+        BSA_GATHER_HALF_LO(v_rsrc, origin_0, v_lds0_a);
+        BSA_GATHER_HALF_HI(v_rsrc, origin_0, v_lds1_a);
     }
 
     // Q as B operand of S^T = K Q^T: lane (query l32 + 32 nt, half) holds
@@ -402,16 +439,32 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
         if (++pct == subs) { pct = 0; ++pcb; }
         return origin_of(block_at(pcb <= n ? pcb : n)) + (uint32_t)(sub_tile_first(g, pct) * (D * 2));
     };
-    uint32_t o1 = next_origin();                       // origin of pair c + 1
+    // K or V of pair c, or the descriptor that loads nothing past the last pair
+    auto k_of = [&](int c) { return c < pairs ? k_rsrc : null_rsrc; };
+    auto v_of = [&](int c) { return c < pairs ? v_rsrc : null_rsrc; };
+    uint32_t o_far = next_origin();                    // origin of pair c + DEPTH (here: pair 1)
 
-    // ---- pipeline prologue: fragments of pair 0, refill of K half 0, S tile 0
+    // ---- pipeline prologue: with DEPTH 2 all of pair 1 follows pair 0 into LDS
+    // (set b); fragments of pair 0; K half 0 of pair DEPTH into the buffer just
+    // read; S tile 0
     f32x16 s[2];            // S^T tiles, by query half
     bf16x8 p[2][2];         // P^T tiles, by query half; [h]: keys 16 h .. 16 h + 15 of the tile
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (DEPTH == 2) {
+        BSA_GATHER_HALF_LO(k_of(1), o_far, k_lds0_b);
+        BSA_GATHER_HALF_HI(k_of(1), o_far, k_lds1_b);
+        BSA_GATHER_HALF_LO(v_of(1), o_far, v_lds0_b);
+        BSA_GATHER_HALF_HI(v_of(1), o_far, v_lds1_b);
+        o_far = next_origin();                         // pair 2
+        if (NW == 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        if (NW == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (NW == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     wg_barrier();                                      // pair 0's tiles have landed
-    read_k_half(0, k_lds0);
-    read_k_half(1, k_lds1);
-    read_v_half(0, v_lds0);
+    read_k_half(0, k_lds0_a);
+    read_k_half(1, k_lds1_a);
+    read_v_half(0, v_lds0_a);
     {
         // the first step adds a zero tile to O: weights and V fragments of
         // "tile -1" are zeros
@@ -421,14 +474,9 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     wg_barrier();                                      // everyone has read K half 0
-    {
-        const __amdgpu_buffer_rsrc_t k1 = 1 < pairs ? k_rsrc : null_rsrc;
-        BSA_GATHER_MINE(0, k1, o1, k_lds0);
-        BSA_GATHER_MINE(1, k1, o1, k_lds0);
-        BSA_GATHER_MINE(2, k1, o1, k_lds0);
-        BSA_GATHER_MINE(3, k1, o1, k_lds0);
-    }
-#undef BSA_GATHER_MINE
+    BSA_GATHER_HALF_LO(k_of(DEPTH), o_far, k_lds0_a);
+#undef BSA_GATHER_HALF_LO
+#undef BSA_GATHER_HALF_HI
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[0][ks],
@@ -452,59 +500,83 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
         return tile_weights(s[nt], c2, -m_new, p[nt]);
     };
 
-    for (int c = 0; c < pairs; ++c) {
-        const uint32_t o2 = next_origin();             // origin of pair c + 2
-        const __amdgpu_buffer_rsrc_t k1 = c + 1 < pairs ? k_rsrc : null_rsrc;
-        const __amdgpu_buffer_rsrc_t v1 = c + 1 < pairs ? v_rsrc : null_rsrc;
-        const __amdgpu_buffer_rsrc_t k2 = c + 2 < pairs ? k_rsrc : null_rsrc;
+    // One pair, c, whose tiles are in LDS set SET (pair c + 1: set SET ^ (DEPTH - 1)).
+    // On entry o_far is the origin of pair c + DEPTH.  Loads in flight on entry
+    // (DEPTH 1 / 2): K half 0 of pair c + 1 / c + 2; with DEPTH 2 also all of
+    // pair c + 1.  A buffer is refilled, right after its fragments were read,
+    // with the same half of the pair DEPTH (K half 0: DEPTH + 1) further on,
+    // which then has three (DEPTH 2: seven) steps to arrive.
+    auto one_pair = [&](int c, auto set_tag) {
+        constexpr int SET = decltype(set_tag)::value;
+        constexpr int NXT = DEPTH == 2 ? SET ^ 1 : 0;          // set of pair c + 1
+        unsigned char* const k1_cur = SET == 0 ? k_lds1_a : k_lds1_b;
+        unsigned char* const v0_cur = SET == 0 ? v_lds0_a : v_lds0_b;
+        unsigned char* const v1_cur = SET == 0 ? v_lds1_a : v_lds1_b;
+        unsigned char* const k0_nxt = NXT == 0 ? k_lds0_a : k_lds0_b;
+        unsigned char* const k1_nxt = NXT == 0 ? k_lds1_a : k_lds1_b;
+        unsigned char* const v0_nxt = NXT == 0 ? v_lds0_a : v_lds0_b;
+        const uint32_t o_a = o_far;                    // origin of pair c + DEPTH
+        const uint32_t o_b = next_origin();            // origin of pair c + DEPTH + 1
+        const __amdgpu_buffer_rsrc_t k_a = k_of(c + DEPTH), v_a = v_of(c + DEPTH);
+        const __amdgpu_buffer_rsrc_t k_b = k_of(c + DEPTH + 1);
         Refill rf;
         float rs;
 
         // ---- step 0: weights of tile (0,0); S of (0,1); O += tile (1,1) of the
-        // previous pair.  K half 1 and V half 0 were read in the previous step
-        // 3: refill them with pair c+1.
+        // previous pair.  K half 1 and V half 0 of this pair were read in the
+        // previous step 3: refill them with pair c + DEPTH.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         wg_barrier();
-        rf = Refill{v1, k1, o1, o1, LDS_PTR(unsigned char, v_lds0), LDS_PTR(unsigned char, k_lds1)};
-        rs = pipeline_step<0, true, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, wave,
+        rf = Refill{v_a, k_a, o_a, o_a, LDS_PTR(unsigned char, v0_cur), LDS_PTR(unsigned char, k1_cur)};
+        rs = pipeline_step<0, true, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, wave_kib,
                                         [] {});
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(0);
         l_run[0] += rs;
 
         // ---- step 1: weights of (0,1); S of (1,0); O += tile (0,0).  K half 0
-        // of pair c+1 and V half 1 of pair c have landed (everything older than
-        // the last 8 loads): read their fragments.
-        rs = pipeline_step<1, false, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, wave, [&] {
+        // of pair c+1 and V half 1 of pair c have landed: read their fragments.
+        rs = pipeline_step<1, false, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, wave_kib, [&] {
             wait_older_loads();
             wg_barrier();
-            read_k_half(0, k_lds0);
-            read_v_half(1, v_lds1);
+            read_k_half(0, k0_nxt);
+            read_v_half(1, v1_cur);
         });
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(1);
         l_run[1] += rs;
 
-        // ---- step 2: weights of (1,0); S of (1,1); O += tile (0,1).  Refill K
-        // half 0 with pair c+2 and V half 1 with pair c+1.
+        // ---- step 2: weights of (1,0); S of (1,1); O += tile (0,1).  Refill the
+        // two buffers just read: K half 0 with pair c + DEPTH + 1, V half 1 with
+        // pair c + DEPTH.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         wg_barrier();
-        rf = Refill{k2, v1, o2, o1, LDS_PTR(unsigned char, k_lds0), LDS_PTR(unsigned char, v_lds1)};
-        rs = pipeline_step<2, true, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, wave,
+        rf = Refill{k_b, v_a, o_b, o_a, LDS_PTR(unsigned char, k0_nxt), LDS_PTR(unsigned char, v1_cur)};
+        rs = pipeline_step<2, true, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[0], rf, voff, wave_kib,
                                         [] {});
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(0);
         l_run[0] += rs;
 
         // ---- step 3: weights of (1,1); S of tile (0,0) of pair c+1; O += tile
         // (1,0).  K half 1 and V half 0 of pair c+1 have landed: read them.
-        rs = pipeline_step<3, false, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, wave, [&] {
+        rs = pipeline_step<3, false, NW>(s, p, oacc, qf, kf, vf, c2, -m_ref[1], rf, voff, wave_kib, [&] {
             wait_older_loads();
             wg_barrier();
-            read_k_half(1, k_lds1);
-            read_v_half(0, v_lds0);
+            read_k_half(1, k1_nxt);
+            read_v_half(0, v0_nxt);
         });
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs <= kSumLimit)) != 0, 0)) rs = repair(1);
         l_run[1] += rs;
 
-        o1 = o2;
+        o_far = o_b;
+    };
+    if (DEPTH == 1) {
+        for (int c = 0; c < pairs; ++c) one_pair(c, SetTag<0>{});
+    } else {
+        // (two tiles are kept only by workgroups of 2 or 4 wavefronts, whose
+        // blocks have an even number of 64-key sub-tiles: pairs is even)
+        for (int c = 0; c < pairs; c += 2) {
+            one_pair(c, SetTag<0>{});
+            one_pair(c + 1, SetTag<1>{});
+        }
     }
 
     // ---- pipeline epilogue: O += tile (1,1) of the last pair
@@ -539,18 +611,20 @@ __device__ __forceinline__ void fwd_mfma_d64_body(
 }
 
 // One kernel per workgroup size (plain functions: the body is the template).
-#define BSA_FWD_D64_KERNEL(NAME, NW)                                                              \
+// Workgroups of 2 or 4 wavefronts keep two K/V tiles in LDS (32 KiB: the CU's
+// LDS still holds its 8 wavefronts); a lone wavefront keeps one.
+#define BSA_FWD_D64_KERNEL(NAME, NW, DEPTH)                                                       \
     __global__ __launch_bounds__(64 * NW, 2) void NAME(                                           \
         const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,                           \
         const uint16_t* __restrict__ v, const int32_t* __restrict__ sel_idx,                      \
         uint16_t* __restrict__ out, float* __restrict__ lse, Geom g, uint32_t n_units,            \
         int subs)                                                                                 \
     {                                                                                             \
-        fwd_mfma_d64_body<NW>(q, k, v, sel_idx, out, lse, g, n_units, subs);                      \
+        fwd_mfma_d64_body<NW, DEPTH>(q, k, v, sel_idx, out, lse, g, n_units, subs);               \
     }
-BSA_FWD_D64_KERNEL(fwd_mfma_b64_d64_kernel, 1)
-BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg2_kernel, 2)
-BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg4_kernel, 4)
+BSA_FWD_D64_KERNEL(fwd_mfma_b64_d64_kernel, 1, 1)
+BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg2_kernel, 2, 2)
+BSA_FWD_D64_KERNEL(fwd_mfma_d64_wg4_kernel, 4, 2)
 #undef BSA_FWD_D64_KERNEL
 
 bool fwd_mfma_supported(bool is_bf16, const Geom& g, int D)
